@@ -1,0 +1,189 @@
+/*
+ * spec_verify.h - C ABI of the MI355X (gfx950) parallel-verification library.
+ *
+ * The library implements the verification step of speculative inference as stated
+ * in Section 2.1 of the CoSine paper (arXiv 2503.10325) plus the confidence-based
+ * token fusion of its Section 4.2:
+ *
+ *   spec_verify_attn   the attention sub-step of the target model's parallel pass
+ *                      over all draft tokens (Section 2.1; tree attention, Sections
+ *                      2.1 and 4.2),
+ *   spec_fuse_drafts   token fusion across drafters (Algorithm 1, TokenFusion;
+ *                      Eq. 4, first line),
+ *   spec_accept        acceptance-rejection with residual resampling and the bonus
+ *                      token (Section 2.1).
+ *
+ * Conventions common to every entry point
+ *   - Pointers are DEVICE pointers unless the comment says "host".
+ *   - The caller owns every buffer (inputs, outputs, workspace).  The library
+ *     allocates nothing, frees nothing and keeps no pointer after returning.
+ *   - Calls validate their host-visible arguments, enqueue kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and return without
+ *     synchronising.  Outputs are valid once the stream has been synchronised.
+ *   - Return value: SPEC_OK (0) or a negative spec_status.  Nothing is enqueued when
+ *     validation fails.  Data that lives on the device (parent[], block_table[],
+ *     token ids) is NOT validated: out-of-range page or token indices are undefined
+ *     behaviour; a parent[i] outside [-1, i) is treated as -1.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point
+ *     atomics are used in any reduction).
+ *   - bf16 tensors are raw 16-bit patterns; all arithmetic is fp32/fp64 on exact
+ *     upcasts (attention feeds bf16 operands to the matrix cores, accumulating in
+ *     fp32).
+ */
+#ifndef SPEC_VERIFY_H
+#define SPEC_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPEC_OK = 0,
+  SPEC_ERR_NULL = -1,        /* a required pointer is NULL                        */
+  SPEC_ERR_SHAPE = -2,       /* a size is negative, zero where it may not be, or inconsistent */
+  SPEC_ERR_UNSUPPORTED = -3, /* head_dim / page_size / dtype / mode not implemented */
+  SPEC_ERR_WORKSPACE = -4,   /* workspace missing or smaller than *_workspace_size */
+  SPEC_ERR_LAUNCH = -6       /* the HIP runtime refused a launch                   */
+} spec_status;
+
+typedef enum { SPEC_BF16 = 0, SPEC_F32 = 1 } spec_dtype;
+
+/* ------------------------------------------------------------------------------
+ * spec_verify_attn
+ *
+ * For request b (of `batch`), query head h and draft node i (of n[b] =
+ * q_offsets[b+1]-q_offsets[b] nodes):
+ *
+ *   O[i,h,:] = sum_t softmax_t( scale * <Q[i,h,:], K[t,h/G,:]> ) * V[t,h/G,:]
+ *
+ * where t runs over the ctx_len[b] committed positions and over the draft
+ * positions ctx_len[b]+j of node i itself and of its ancestors (a linear draft:
+ * j <= i).  G = num_q_heads / num_kv_heads.  Draft node j's key/value are expected
+ * in the cache at logical position ctx_len[b]+j before the call.
+ * ---------------------------------------------------------------------------- */
+typedef struct {
+  int32_t batch;             /* B >= 0                                              */
+  int32_t num_q_heads;       /* Hq                                                  */
+  int32_t num_kv_heads;      /* Hkv, Hq % Hkv == 0                                  */
+  int32_t head_dim;          /* D: 64 or 128                                        */
+  int32_t page_size;         /* tokens per cache page: 16                           */
+  int32_t total_q;           /* sum_b n[b] = q_offsets[B]                           */
+  int32_t max_q_per_req;     /* upper bound of n[b]; at most 64                     */
+  int32_t max_pages_per_req; /* row stride of block_table; >= ceil((ctx+n)/page)    */
+  int64_t total_kv_tokens_hint; /* host's estimate of sum_b (ctx_len[b]+n[b]); 0 = unknown.
+                                   Only steers how the context is split into chunks. */
+  float scale;               /* softmax scale; 0 selects 1/sqrt(head_dim)           */
+  int32_t out_dtype;         /* spec_dtype of `out`: SPEC_BF16 or SPEC_F32          */
+} spec_attn_desc;
+
+/* Bytes of workspace spec_verify_attn needs for this descriptor (host call). */
+size_t spec_verify_attn_workspace_size(const spec_attn_desc* desc);
+
+int32_t spec_verify_attn(
+    const spec_attn_desc* desc,  /* host                                              */
+    const void* q,               /* [total_q, Hq, D] bf16                             */
+    const void* k_pool,          /* [num_pages, Hkv, page_size, D] bf16               */
+    const void* v_pool,          /* [num_pages, Hkv, page_size, D] bf16               */
+    const int32_t* block_table,  /* [B, max_pages_per_req] logical page -> pool page  */
+    const int32_t* ctx_len,      /* [B]                                               */
+    const int32_t* q_offsets,    /* [B+1] prefix sums of n[b]                         */
+    const int32_t* parent,       /* [total_q] parent node within the request, -1 = child of
+                                    the committed prefix, parent[i] < i; NULL = linear  */
+    void* out,                   /* [total_q, Hq, D] of out_dtype                     */
+    float* lse,                  /* optional [total_q, Hq]: natural-log sum-exp of the
+                                    scaled scores over the allowed set; may be NULL    */
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------
+ * spec_fuse_drafts
+ *
+ * Position i of request b holds one candidate token per drafter n with the
+ * probability conf[b,i,n] that drafter assigned to it.  ARGMAX (the paper's rule):
+ * winner = argmax_n conf (lowest n on ties), fused_token = that drafter's token,
+ * q_row = (b*k_max+i)*N + winner, the row of draft_logits the token was drawn from.
+ * MIXTURE (weighted averaging of distributions, Section 2.2): additionally
+ * fused_probs[b*k_max+i, :] = sum_n w_n softmax(draft_logits[(b,i,n)] / T),
+ * w_n = conf_n / sum_n conf_n (1/N when all are zero) and q_row = b*k_max+i.
+ * Positions i >= k_len[b] get -1 in the three index outputs (fused_probs rows of
+ * such positions are left untouched).
+ * ---------------------------------------------------------------------------- */
+typedef enum { SPEC_FUSE_ARGMAX = 0, SPEC_FUSE_MIXTURE = 1 } spec_fuse_mode;
+
+size_t spec_fuse_drafts_workspace_size(int32_t B, int32_t k_max, int32_t N, int32_t V, int32_t mode);
+
+int32_t spec_fuse_drafts(
+    int32_t B, int32_t k_max, int32_t N, int32_t V,
+    const int32_t* k_len,        /* [B] valid positions per request, <= k_max          */
+    const float* conf,           /* [B, k_max, N]                                      */
+    const int32_t* draft_tokens, /* [B, k_max, N]                                      */
+    const void* draft_logits,    /* [B*k_max*N, V]; may be NULL in ARGMAX mode         */
+    int32_t logits_dtype,        /* spec_dtype of draft_logits                         */
+    float temperature,           /* > 0 (MIXTURE only)                                 */
+    int32_t mode,                /* spec_fuse_mode                                     */
+    int32_t* fused_token,        /* [B, k_max]                                         */
+    int32_t* winner,             /* [B, k_max]                                         */
+    int32_t* q_row,              /* [B, k_max]                                         */
+    float* fused_probs,          /* MIXTURE: [B*k_max, V] fp32; else may be NULL       */
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------
+ * spec_accept
+ *
+ * Request b owns draft nodes node_offsets[b] .. node_offsets[b+1]) and target rows
+ * node_offsets[b]+b ..: local row 0 is the target distribution after the committed
+ * prefix, local row 1+j the one after node j.  p = softmax(target row / T);
+ * q = softmax(draft row / T) (SPEC_Q_LOGITS) or the row itself (SPEC_Q_PROBS).
+ *
+ * Walk from the committed prefix: r = p of the current node.  For each child c of
+ * the current node in index order, accept when u_accept[c] < r(x_c)/q(x_c) - so
+ * q <= r always accepts and otherwise the token is rejected with probability
+ * 1 - r/q - and descend; on rejection r <- norm(max(0, r - q)) and the next sibling
+ * is tried.  When the current node has no child (everything accepted) or all its
+ * children were rejected, one token is drawn from r by inverse CDF in ascending
+ * token order with u_resample[b]: the smallest t with sum_{v<=t} r_v > u * sum_v r_v.
+ * For a linear draft this is exactly the rule of Section 2.1; siblings must be
+ * i.i.d. draws from one draft row (they share q_row).  q(x)=0<r(x) accepts,
+ * q(x)=r(x)=0 rejects; a residual of zero mass leaves r unchanged.
+ * ---------------------------------------------------------------------------- */
+typedef enum { SPEC_Q_LOGITS = 0, SPEC_Q_PROBS = 1 } spec_q_kind;
+
+size_t spec_accept_workspace_size(int32_t B, int32_t total_nodes, int32_t n_q_rows, int32_t V);
+
+int32_t spec_accept(
+    int32_t B, int32_t V,
+    int32_t total_nodes,         /* = node_offsets[B] (host copy)                      */
+    int32_t n_q_rows,            /* rows of draft_q                                    */
+    int32_t max_nodes_per_req,   /* upper bound of n[b]; at most 64                    */
+    const int32_t* node_offsets, /* [B+1]                                              */
+    const int32_t* parent,       /* [total_nodes] or NULL = linear chain               */
+    const int32_t* draft_tokens, /* [total_nodes] in [0, V)                            */
+    const void* target_logits,   /* [total_nodes + B, V]                               */
+    int32_t target_dtype,        /* spec_dtype                                         */
+    const void* draft_q,         /* [n_q_rows, V]                                      */
+    int32_t q_dtype,             /* spec_dtype                                         */
+    int32_t q_kind,              /* spec_q_kind                                        */
+    const int32_t* q_row,        /* [total_nodes] row of draft_q node j was drawn from */
+    float temperature,           /* > 0                                                */
+    const float* u_accept,       /* [total_nodes] in [0,1)                             */
+    const float* u_resample,     /* [B] in [0,1)                                       */
+    int32_t* accept_len,         /* [B] number of accepted draft tokens                */
+    int32_t* out_tokens,         /* [B, out_stride]: accepted tokens, then the drawn one;
+                                    entries past accept_len[b]+1 are set to -1          */
+    int32_t out_stride,          /* >= max_nodes_per_req + 1                           */
+    int32_t* stop_node,          /* optional [B]: last accepted node or -1             */
+    float* dbg_ratio,            /* optional [total_nodes]: ratio compared at each visited
+                                    node, NaN where not visited                         */
+    void* workspace, size_t workspace_bytes, void* stream);
+
+const char* spec_strerror(int32_t status);
+
+/* Library/ABI version, bumped when a signature changes. */
+int32_t spec_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_VERIFY_H */

@@ -1,0 +1,164 @@
+"""Thin ctypes binding of libspecverify.so (include/spec_verify.h).
+
+Argument marshalling only: every step of the verification path runs inside the
+library's HIP kernels.  PyTorch is used for device memory and the current stream.
+There is no CPU fallback; importing works without the library, calling does not.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecverify.so")
+
+SPEC_OK = 0
+SPEC_BF16, SPEC_F32 = 0, 1
+SPEC_FUSE_ARGMAX, SPEC_FUSE_MIXTURE = 0, 1
+SPEC_Q_LOGITS, SPEC_Q_PROBS = 0, 1
+
+EXPORTS = [
+    "spec_verify_attn_workspace_size", "spec_verify_attn",
+    "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
+    "spec_accept_workspace_size", "spec_accept",
+    "spec_strerror", "spec_abi_version",
+]
+
+
+class SpecAttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32), ("total_q", ctypes.c_int32),
+        ("max_q_per_req", ctypes.c_int32), ("max_pages_per_req", ctypes.c_int32),
+        ("total_kv_tokens_hint", ctypes.c_int64), ("scale", ctypes.c_float), ("out_dtype", ctypes.c_int32),
+    ]
+
+
+class SpecError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: {status} ({strerror(status)})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+        L.spec_strerror.restype = ctypes.c_char_p
+        L.spec_strerror.argtypes = [i32]
+        L.spec_abi_version.restype = i32
+        L.spec_verify_attn_workspace_size.restype = sz
+        L.spec_verify_attn_workspace_size.argtypes = [ctypes.POINTER(SpecAttnDesc)]
+        L.spec_verify_attn.restype = i32
+        L.spec_verify_attn.argtypes = [ctypes.POINTER(SpecAttnDesc)] + [vp] * 10 + [sz, vp]
+        L.spec_fuse_drafts_workspace_size.restype = sz
+        L.spec_fuse_drafts_workspace_size.argtypes = [i32] * 5
+        L.spec_fuse_drafts.restype = i32
+        L.spec_fuse_drafts.argtypes = [i32] * 4 + [vp] * 4 + [i32, f32, i32] + [vp] * 5 + [sz, vp]
+        L.spec_accept_workspace_size.restype = sz
+        L.spec_accept_workspace_size.argtypes = [i32] * 4
+        L.spec_accept.restype = i32
+        L.spec_accept.argtypes = ([i32] * 5 + [vp] * 4 + [i32, vp, i32, i32, vp, f32] + [vp] * 4 + [i32]
+                                  + [vp] * 3 + [sz, vp])
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().spec_strerror(int(status)).decode()
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    assert t.is_contiguous(), "tensors handed to the library must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return SPEC_BF16
+    if t.dtype == torch.float32:
+        return SPEC_F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def make_attn_desc(batch, num_q_heads, num_kv_heads, head_dim, total_q, max_q_per_req, max_pages_per_req,
+                   total_kv_tokens_hint=0, scale=0.0, out_dtype=SPEC_BF16, page_size=16) -> SpecAttnDesc:
+    return SpecAttnDesc(batch, num_q_heads, num_kv_heads, head_dim, page_size, total_q, max_q_per_req,
+                        max_pages_per_req, total_kv_tokens_hint, scale, out_dtype)
+
+
+def spec_verify_attn_workspace_size(desc: SpecAttnDesc) -> int:
+    return int(lib().spec_verify_attn_workspace_size(ctypes.byref(desc)))
+
+
+def spec_verify_attn(desc: SpecAttnDesc, q, k_pool, v_pool, block_table, ctx_len, q_offsets, parent, out,
+                     lse=None, workspace=None, stream=None) -> None:
+    """Device tensors: q/k_pool/v_pool bf16, block_table/ctx_len/q_offsets/parent int32, out bf16 or
+    fp32, lse fp32 or None, workspace uint8 of at least spec_verify_attn_workspace_size(desc) bytes."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_verify_attn(ctypes.byref(desc), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                _ptr(ctx_len), _ptr(q_offsets), _ptr(parent), _ptr(out), _ptr(lse),
+                                _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_verify_attn", rc)
+
+
+def spec_fuse_drafts_workspace_size(B, k_max, N, V, mode) -> int:
+    return int(lib().spec_fuse_drafts_workspace_size(B, k_max, N, V, mode))
+
+
+def spec_fuse_drafts(k_len, conf, draft_tokens, draft_logits, temperature, mode, fused_token, winner, q_row,
+                     fused_probs=None, workspace=None, stream=None, V: Optional[int] = None) -> None:
+    """conf/draft_tokens [B,k_max,N]; draft_logits [B*k_max*N, V] or None (ARGMAX)."""
+    B, k_max, N = conf.shape
+    if draft_logits is not None:
+        V = draft_logits.shape[1]
+        ldt = _dtype_code(draft_logits)
+    else:
+        V, ldt = (V or 0), SPEC_BF16
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_fuse_drafts(B, k_max, N, V, _ptr(k_len), _ptr(conf), _ptr(draft_tokens), _ptr(draft_logits),
+                                ldt, float(temperature), int(mode), _ptr(fused_token), _ptr(winner), _ptr(q_row),
+                                _ptr(fused_probs), _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_fuse_drafts", rc)
+
+
+def spec_accept_workspace_size(B, total_nodes, n_q_rows, V) -> int:
+    return int(lib().spec_accept_workspace_size(B, total_nodes, n_q_rows, V))
+
+
+def spec_accept(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_tokens, target_logits, draft_q,
+                q_kind, q_row, temperature, u_accept, u_resample, accept_len, out_tokens, stop_node=None,
+                dbg_ratio=None, workspace=None, stream=None) -> None:
+    """target_logits [total_nodes+B, V], draft_q [n_q_rows, V] (bf16 or fp32 device tensors);
+    out_tokens [B, out_stride] int32."""
+    V = target_logits.shape[1]
+    n_q_rows = 0 if draft_q is None else draft_q.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_accept(B, V, total_nodes, n_q_rows, max_nodes_per_req, _ptr(node_offsets), _ptr(parent),
+                           _ptr(draft_tokens), _ptr(target_logits), _dtype_code(target_logits), _ptr(draft_q),
+                           SPEC_BF16 if draft_q is None else _dtype_code(draft_q), int(q_kind), _ptr(q_row),
+                           float(temperature), _ptr(u_accept), _ptr(u_resample), _ptr(accept_len),
+                           _ptr(out_tokens), out_tokens.shape[1], _ptr(stop_node), _ptr(dbg_ratio),
+                           _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_accept", rc)

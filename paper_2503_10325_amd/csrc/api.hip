@@ -1,0 +1,137 @@
+// C ABI of the verification library: argument validation and dispatch only.
+#include "../../include/spec_verify.h"
+
+#include "kernels.h"
+
+using namespace specv;
+
+extern "C" {
+
+const char* spec_strerror(int32_t status) {
+  switch (status) {
+    case SPEC_OK: return "ok";
+    case SPEC_ERR_NULL: return "a required pointer is NULL";
+    case SPEC_ERR_SHAPE: return "invalid or inconsistent size";
+    case SPEC_ERR_UNSUPPORTED: return "unsupported head_dim, page_size, dtype or mode";
+    case SPEC_ERR_WORKSPACE: return "workspace missing or too small";
+    case SPEC_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t spec_abi_version(void) { return 1; }
+
+static int check_attn_desc(const spec_attn_desc* d) {
+  if (!d) return SPEC_ERR_NULL;
+  if (d->batch < 0 || d->total_q < 0 || d->num_q_heads <= 0 || d->num_kv_heads <= 0 ||
+      d->max_pages_per_req < 0 || d->max_q_per_req < 0)
+    return SPEC_ERR_SHAPE;
+  if (d->num_q_heads % d->num_kv_heads != 0) return SPEC_ERR_SHAPE;
+  if (d->head_dim != 64 && d->head_dim != 128) return SPEC_ERR_UNSUPPORTED;
+  if (d->page_size != 16) return SPEC_ERR_UNSUPPORTED;
+  if (d->max_q_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (d->out_dtype != SPEC_BF16 && d->out_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
+  if (d->batch > 65535 || d->num_kv_heads > 65535) return SPEC_ERR_UNSUPPORTED;
+  if (d->batch > 0 && d->total_q > 0 && (d->max_pages_per_req == 0 || d->max_q_per_req == 0))
+    return SPEC_ERR_SHAPE;
+  return SPEC_OK;
+}
+
+static AttnArgs attn_args_from(const spec_attn_desc* d) {
+  AttnArgs a{};
+  a.B = d->batch; a.Hq = d->num_q_heads; a.Hkv = d->num_kv_heads; a.D = d->head_dim;
+  a.page = d->page_size; a.total_q = d->total_q; a.max_q = d->max_q_per_req;
+  a.max_pages = d->max_pages_per_req; a.kv_hint = d->total_kv_tokens_hint;
+  a.scale = d->scale; a.out_dtype = d->out_dtype;
+  return a;
+}
+
+size_t spec_verify_attn_workspace_size(const spec_attn_desc* desc) {
+  if (check_attn_desc(desc) != SPEC_OK) return 0;
+  return attn_workspace_bytes(attn_args_from(desc));
+}
+
+int32_t spec_verify_attn(const spec_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                         const int32_t* block_table, const int32_t* ctx_len, const int32_t* q_offsets,
+                         const int32_t* parent, void* out, float* lse, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  const int rc = check_attn_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (desc->batch == 0 || desc->total_q == 0) return SPEC_OK;
+  if (!q || !k_pool || !v_pool || !block_table || !ctx_len || !q_offsets || !out) return SPEC_ERR_NULL;
+  AttnArgs a = attn_args_from(desc);
+  if (a.scale == 0.f) a.scale = 1.0f / sqrtf(static_cast<float>(a.D));
+  const size_t need = attn_workspace_bytes(a);
+  if (need > 256 && (!workspace || workspace_bytes < need)) return SPEC_ERR_WORKSPACE;
+  a.q = q; a.k_pool = k_pool; a.v_pool = v_pool; a.block_table = block_table; a.ctx_len = ctx_len;
+  a.q_offsets = q_offsets; a.parent = parent; a.out = out; a.lse = lse; a.workspace = workspace;
+  return launch_attn(a, static_cast<hipStream_t>(stream));
+}
+
+size_t spec_fuse_drafts_workspace_size(int32_t B, int32_t k_max, int32_t N, int32_t V, int32_t mode) {
+  if (B < 0 || k_max < 0 || N <= 0 || V < 0) return 0;
+  return fuse_workspace_bytes(B, k_max, N, V, mode);
+}
+
+int32_t spec_fuse_drafts(int32_t B, int32_t k_max, int32_t N, int32_t V, const int32_t* k_len,
+                         const float* conf, const int32_t* draft_tokens, const void* draft_logits,
+                         int32_t logits_dtype, float temperature, int32_t mode, int32_t* fused_token,
+                         int32_t* winner, int32_t* q_row, float* fused_probs, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (B < 0 || k_max < 0 || N <= 0) return SPEC_ERR_SHAPE;
+  if (mode != SPEC_FUSE_ARGMAX && mode != SPEC_FUSE_MIXTURE) return SPEC_ERR_UNSUPPORTED;
+  if (B == 0 || k_max == 0) return SPEC_OK;
+  if (!k_len || !conf || !draft_tokens || !fused_token || !winner || !q_row) return SPEC_ERR_NULL;
+  if (static_cast<int64_t>(B) * k_max * N > INT32_MAX) return SPEC_ERR_SHAPE;
+  if (mode == SPEC_FUSE_MIXTURE) {
+    if (V <= 0 || !(temperature > 0.f)) return SPEC_ERR_SHAPE;
+    if (logits_dtype != SPEC_BF16 && logits_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
+    if (!draft_logits || !fused_probs) return SPEC_ERR_NULL;
+    const size_t need = fuse_workspace_bytes(B, k_max, N, V, mode);
+    if (!workspace || workspace_bytes < need) return SPEC_ERR_WORKSPACE;
+  }
+  FuseArgs a{};
+  a.B = B; a.k_max = k_max; a.N = N; a.V = V; a.k_len = k_len; a.conf = conf; a.draft_tokens = draft_tokens;
+  a.draft_logits = draft_logits; a.l_dtype = logits_dtype; a.temperature = temperature; a.mode = mode;
+  a.fused_token = fused_token; a.winner = winner; a.q_row = q_row; a.fused_probs = fused_probs;
+  a.workspace = workspace;
+  launch_fuse(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
+size_t spec_accept_workspace_size(int32_t B, int32_t total_nodes, int32_t n_q_rows, int32_t V) {
+  if (B < 0 || total_nodes < 0 || n_q_rows < 0 || V <= 0) return 0;
+  return accept_workspace_bytes(B, total_nodes, n_q_rows, V);
+}
+
+int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
+                    const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+                    const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
+                    int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
+                    const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
+                    int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  if (B < 0 || V <= 0 || total_nodes < 0 || n_q_rows < 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
+  if (!(temperature > 0.f)) return SPEC_ERR_SHAPE;
+  if (max_nodes_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (out_stride < max_nodes_per_req + 1) return SPEC_ERR_SHAPE;
+  if ((target_dtype != SPEC_BF16 && target_dtype != SPEC_F32) || (q_dtype != SPEC_BF16 && q_dtype != SPEC_F32))
+    return SPEC_ERR_UNSUPPORTED;
+  if (q_kind != SPEC_Q_LOGITS && q_kind != SPEC_Q_PROBS) return SPEC_ERR_UNSUPPORTED;
+  if (total_nodes > 0 && n_q_rows == 0) return SPEC_ERR_SHAPE;
+  if (B == 0) return SPEC_OK;
+  if (!node_offsets || !target_logits || !u_resample || !accept_len || !out_tokens) return SPEC_ERR_NULL;
+  if (total_nodes > 0 && (!draft_tokens || !draft_q || !q_row || !u_accept)) return SPEC_ERR_NULL;
+  const size_t need = accept_workspace_bytes(B, total_nodes, n_q_rows, V);
+  if (!workspace || workspace_bytes < need) return SPEC_ERR_WORKSPACE;
+  AcceptArgs a{};
+  a.B = B; a.V = V; a.total_nodes = total_nodes; a.n_q_rows = n_q_rows; a.node_offsets = node_offsets;
+  a.parent = parent; a.draft_tokens = draft_tokens; a.target = target_logits; a.t_dtype = target_dtype;
+  a.draft_q = draft_q; a.q_dtype = q_dtype; a.q_kind = q_kind; a.q_row = q_row; a.temperature = temperature;
+  a.u_accept = u_accept; a.u_resample = u_resample; a.accept_len = accept_len; a.out_tokens = out_tokens;
+  a.out_stride = out_stride; a.stop_node = stop_node; a.dbg_ratio = dbg_ratio; a.workspace = workspace;
+  launch_accept(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
+}  // extern "C"

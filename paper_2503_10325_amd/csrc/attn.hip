@@ -1,0 +1,582 @@
+// Verify-attention for gfx950: the draft queries of each request attend over the paged
+// bf16 KV cache (committed context + their draft ancestors), Section 2.1 / 4.2 of the
+// paper (parallel verification with a tree-attention mask).
+//
+// Work decomposition.  One workgroup (4 waves) per (request, KV head, context chunk,
+// row group).  All n*G query rows that share a KV head are processed together so every
+// K/V byte is fetched once per KV head.  Inside the workgroup every wave streams its own
+// 32-token tiles (2 cache pages): coalesced 16-byte global loads -> registers -> the
+// wave's private LDS tile -> MFMA operands.  S^T = K Q^T and O^T = V^T P^T run on
+// v_mfma_f32_32x32x16_bf16 with the tokens as the M dimension, so each lane owns one
+// query column and the online-softmax statistics need a single cross-lane exchange.
+// V is transposed on its way into LDS (token pairs packed with v_perm).  The waves'
+// partial results are merged through LDS; when a request spans several chunks the
+// workgroup writes an unnormalised partial and attn_combine_kernel merges the chunks.
+#include "common.h"
+#include "kernels.h"
+
+namespace specv {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnWaves = 4;
+constexpr int kTile = 32;          // tokens per wave iteration
+constexpr int kPage = 16;
+constexpr int kMaxQ = 64;
+
+template <int D>
+struct AttnCfg {
+  static constexpr int kCh = D / 8;                       // 16-byte chunks per token row
+  static constexpr int kTokPerLoad = 64 / kCh;            // token rows one wave-wide load covers
+  static constexpr int kLoads = kTile / kTokPerLoad;      // loads per tile per tensor (8 / 4)
+  static constexpr int kKStride = D * 2 + 16;             // bytes; padded K row in LDS
+  static constexpr int kKBytes = kTile * kKStride;
+  static constexpr int kVStride = 80;                     // bytes; one V^T row = 32 tokens + pad
+  static constexpr int kVRows = 7 * 18 + D / 8;           // row index sigma(d) = (d%8)*18 + d/8
+  static constexpr int kVBytes = kVRows * kVStride;
+  static constexpr int kWaveLds = kKBytes + kVBytes;
+  static constexpr int kQKSteps = D / 16;
+  static constexpr int kDBlocks = D / 32;
+  static constexpr int kPagesPerLoad = 16 / kCh;          // pages one round of V loads covers: 1 (D=128) / 2 (D=64)
+  static constexpr int kVPageIters = 2 / kPagesPerLoad;
+  static constexpr int kORedStride = D + 4;               // floats; padded row of the cross-wave reduction
+};
+
+struct AttnParams {
+  const uint16_t* q;
+  const uint16_t* k_pool;
+  const uint16_t* v_pool;
+  const int32_t* block_table;
+  const int32_t* ctx_len;
+  const int32_t* q_offsets;
+  const int32_t* parent;
+  void* out;
+  float* lse;
+  float* ws_o;       // [rows, max_chunks, D] unnormalised partial outputs
+  float2* ws_ml;     // [rows, max_chunks] (max in log2 units, sum)
+  int B, Hq, Hkv, G, max_pages, chunk_tokens, max_chunks;
+  float c;           // scale * log2(e)
+  int out_f32;
+};
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
+  union { uint4 u; bf16x8 b; } x;
+  x.u = v;
+  return x.b;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  union { __bf16 h[2]; uint32_t u; } x;
+  x.h[0] = static_cast<__bf16>(lo);
+  x.h[1] = static_cast<__bf16>(hi);
+  return x.u;
+}
+
+template <int D, int NQB>
+__global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P) {
+  using C = AttnCfg<D>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
+
+  const int q0 = P.q_offsets[b];
+  int n = P.q_offsets[b + 1] - q0;
+  n = n > kMaxQ ? kMaxQ : n;
+  if (n <= 0) return;
+  const int ctx = P.ctx_len[b];
+  const int L = ctx + n;
+  const int R = n * P.G;
+  const int row0 = rg * (32 * NQB);
+  if (row0 >= R) return;
+  const int nqb = min(NQB, (R - row0 + 31) / 32);          // active query blocks of this workgroup
+  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+  if (chunk >= nchunks) return;
+  const int cb = (((L + nchunks - 1) / nchunks) + kTile - 1) & ~(kTile - 1);
+  const int t_begin = chunk * cb;
+  const int t_end = min(L, t_begin + cb);
+  const int ntiles = (t_end - t_begin + kTile - 1) / kTile;
+
+  unsigned char* tile_lds = smem + wave * C::kWaveLds;
+  unsigned char* k_lds = tile_lds;
+  unsigned char* v_lds = tile_lds + C::kKBytes;
+  // Small arrays alias the tile memory: the ancestor masks are consumed before the first
+  // tile is staged, the merge statistics live behind the cross-wave reduction buffer.
+  unsigned long long* sh_anc = reinterpret_cast<unsigned long long*>(smem);            // [64]
+  int* sh_par = reinterpret_cast<int*>(smem + 512);                                    // [64]
+  float* sh_m = reinterpret_cast<float*>(smem + kAttnWaves * 32 * C::kORedStride * sizeof(float));  // [4][NQB*32]
+  float* sh_l = sh_m + kAttnWaves * NQB * 32;                                          // [4][NQB*32]
+  float* sh_M = sh_l + kAttnWaves * NQB * 32;                                          // [NQB*32]
+  float* sh_L = sh_M + NQB * 32;                                                       // [NQB*32]
+
+  // ---- ancestor-or-self masks of the draft nodes (only chunks that reach the drafts) ----
+  const bool touches_drafts = t_end > ctx;
+  if (touches_drafts) {
+    if (P.parent) {
+      if (tid < kMaxQ) sh_par[tid] = (tid < n) ? P.parent[q0 + tid] : -1;
+      __syncthreads();
+    }
+    if (tid < kMaxQ) {
+      unsigned long long mask = 0;
+      if (tid < n) {
+        if (P.parent) {
+          int a = tid;
+          for (int g = 0; g <= tid && a >= 0; ++g) {
+            mask |= 1ull << a;
+            const int p = sh_par[a];
+            a = (p >= a || p < -1) ? -1 : p;
+          }
+        } else {
+          mask = (2ull << tid) - 1ull;
+        }
+      }
+      sh_anc[tid] = mask;
+    }
+    __syncthreads();
+  }
+
+  // ---- this lane's query column in every query block ----
+  bf16x8 qf[NQB][C::kQKSteps];
+  unsigned long long my_anc[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int row = row0 + 32 * qb + ln;
+    const bool valid = row < R;
+    const int node = valid ? row / P.G : 0;
+    const int g = valid ? row % P.G : 0;
+    my_anc[qb] = (touches_drafts && valid) ? sh_anc[node] : 0ull;
+    const uint16_t* qp = P.q + (static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + g) * D + 8 * lh;
+#pragma unroll
+    for (int ks = 0; ks < C::kQKSteps; ++ks) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (valid) v = *reinterpret_cast<const uint4*>(qp + 16 * ks);
+      qf[qb][ks] = as_bf16x8(v);
+    }
+  }
+  if (touches_drafts) __syncthreads();       // masks are in registers; the memory becomes tile space
+
+  float m_run[NQB], l_run[NQB];
+  f32x16 oacc[NQB][C::kDBlocks];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
+  }
+
+  // ---- lane roles for the loads ----
+  const int kc = lane % C::kCh;              // 16-byte chunk within the token row
+  const int kt = lane / C::kCh;              // token row within one load instruction
+  // V: each lane loads 4 consecutive tokens (4*va + i) of a page so that the transposed
+  // LDS write packs them into 8 bytes.
+  const int vgrp = lane / C::kCh;
+  const int vg4 = vgrp & 3;
+  const int va = ((vg4 & 1) << 1) | (vg4 >> 1);     // token group within the page
+  const int vs_lane = vgrp >> 2;                     // page within one load (D=64 only)
+  const int vhh = va & 1, vpart = va >> 1;
+
+  const int32_t* bt = P.block_table + static_cast<int64_t>(b) * P.max_pages;
+  const int64_t page_elems = static_cast<int64_t>(P.Hkv) * kPage * D;
+  const int64_t head_off = static_cast<int64_t>(kvh) * kPage * D;
+
+  uint4 kr[C::kLoads], vr[C::kLoads];
+
+  auto issue_loads = [&](int t) {
+    const int tok0 = t_begin + kTile * t;
+    const int lp = tok0 / kPage;
+    int pg[2];
+    pg[0] = bt[lp];
+    pg[1] = (tok0 + kPage < L) ? bt[lp + 1] : -1;
+#pragma unroll
+    for (int j = 0; j < C::kLoads; ++j) {
+      const int tk = j * C::kTokPerLoad + kt;
+      const int page = pg[(j * C::kTokPerLoad) / kPage];
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (page >= 0)
+        v = *reinterpret_cast<const uint4*>(P.k_pool + page * page_elems + head_off + (tk % kPage) * D + kc * 8);
+      kr[j] = v;
+    }
+#pragma unroll
+    for (int pi = 0; pi < C::kVPageIters; ++pi) {
+      const int s = pi * C::kPagesPerLoad + vs_lane;
+      const int page = pg[s];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int slot = 4 * va + i;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (page >= 0 && tok0 + kPage * s + slot < L)      // never multiply stale cache slots into O
+          v = *reinterpret_cast<const uint4*>(P.v_pool + page * page_elems + head_off + slot * D + kc * 8);
+        vr[pi * 4 + i] = v;
+      }
+    }
+  };
+
+  int t = wave;
+  if (t < ntiles) issue_loads(t);
+  for (; t < ntiles; t += kAttnWaves) {
+    // ---- registers -> LDS ----
+#pragma unroll
+    for (int j = 0; j < C::kLoads; ++j) {
+      const int tk = j * C::kTokPerLoad + kt;
+      *reinterpret_cast<uint4*>(k_lds + tk * C::kKStride + kc * 16) = kr[j];
+    }
+#pragma unroll
+    for (int pi = 0; pi < C::kVPageIters; ++pi) {
+      const int s = pi * C::kPagesPerLoad + vs_lane;
+      const uint4 a0 = vr[pi * 4 + 0], a1 = vr[pi * 4 + 1], a2 = vr[pi * 4 + 2], a3 = vr[pi * 4 + 3];
+      const uint32_t w0[4] = {a0.x, a0.y, a0.z, a0.w};
+      const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
+      const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
+      const uint32_t w3[4] = {a3.x, a3.y, a3.z, a3.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const uint32_t sel = half ? 0x07060302u : 0x05040100u;
+          uint2 o;
+          o.x = __builtin_amdgcn_perm(w1[k], w0[k], sel);    // tokens 4va, 4va+1 at dim 8kc+2k+half
+          o.y = __builtin_amdgcn_perm(w3[k], w2[k], sel);    // tokens 4va+2, 4va+3
+          const int vrow = (2 * k + half) * 18 + kc;
+          *reinterpret_cast<uint2*>(v_lds + vrow * C::kVStride + 32 * s + 16 * vhh + 8 * vpart) = o;
+        }
+      }
+    }
+    const int tok0 = t_begin + kTile * t;
+    if (t + kAttnWaves < ntiles) issue_loads(t + kAttnWaves);
+    wave_lds_fence();
+
+    // ---- S^T = K Q^T ----
+    f32x16 sacc[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::kQKSteps; ++ks) {
+      const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(k_lds + ln * C::kKStride + 32 * ks + 16 * lh));
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+        if (qb < nqb) sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[qb], 0, 0, 0);
+    }
+
+    // ---- mask, online softmax, P^T in bf16 ----
+    const bool need_mask = tok0 + kTile > ctx;
+    bf16x8 pf[NQB][2], pl[NQB][2];       // P^T split into two bf16 terms (hi + lo)
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      if (qb < nqb) {
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = sacc[qb][r] * P.c;
+          if (need_mask) {
+            const int pos = tok0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const bool ok = pos < ctx || (pos < L && ((my_anc[qb] >> ((pos - ctx) & 63)) & 1ull));
+            v = ok ? v : -INFINITY;
+          }
+          sacc[qb][r] = v;
+          tmax = fmaxf(tmax, v);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+        const float m_new = fmaxf(m_run[qb], tmax);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run[qb] - m_safe);
+        float psum = 0.f;
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = fast_exp2(sacc[qb][r] - m_safe);
+          psum += p[r];
+        }
+        // A single bf16 rounding of P (2^-9 relative) would dominate the output error; carrying
+        // the rounding residual in a second bf16 term keeps ~16 bits of every weight.
+        union { uint32_t u[4]; bf16x8 v; } f0, f1, g0, g1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t h0 = pack_bf16(p[2 * j], p[2 * j + 1]);
+          const uint32_t h1 = pack_bf16(p[8 + 2 * j], p[8 + 2 * j + 1]);
+          f0.u[j] = h0;
+          f1.u[j] = h1;
+          g0.u[j] = pack_bf16(p[2 * j] - bf16_lo(h0), p[2 * j + 1] - bf16_hi(h0));
+          g1.u[j] = pack_bf16(p[8 + 2 * j] - bf16_lo(h1), p[8 + 2 * j + 1] - bf16_hi(h1));
+        }
+        pf[qb][0] = f0.v;
+        pf[qb][1] = f1.v;
+        pl[qb][0] = g0.v;
+        pl[qb][1] = g1.v;
+        l_run[qb] = l_run[qb] * alpha + psum;
+        m_run[qb] = m_new;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+          for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
+        }
+      }
+    }
+
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int db = 0; db < C::kDBlocks; ++db) {
+      const int d = 32 * db + ln;
+      const int vrow = (d & 7) * 18 + (d >> 3);
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(v_lds + vrow * C::kVStride + 32 * s + 16 * lh));
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+          if (qb < nqb) {
+            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qb][s], oacc[qb][db], 0, 0, 0);
+            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl[qb][s], oacc[qb][db], 0, 0, 0);
+          }
+      }
+    }
+    wave_lds_fence();
+  }
+
+  // ---- merge the four waves ----
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32, kWave);
+  __syncthreads();                         // every wave is done with its tile memory
+  if (lane < 32) {
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      sh_m[wave * NQB * 32 + qb * 32 + lane] = m_run[qb];
+      sh_l[wave * NQB * 32 + qb * 32 + lane] = l_run[qb];
+    }
+  }
+  __syncthreads();
+  float fscale[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, sh_m[w * NQB * 32 + qb * 32 + ln]);
+    float Ls = 0.f;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) {
+      const float mw = sh_m[w * NQB * 32 + qb * 32 + ln];
+      if (mw != -INFINITY) Ls += sh_l[w * NQB * 32 + qb * 32 + ln] * fast_exp2(mw - M);
+    }
+    fscale[qb] = (m_run[qb] == -INFINITY) ? 0.f : fast_exp2(m_run[qb] - M);
+    if (wave == 0 && lane < 32) {
+      sh_M[qb * 32 + lane] = M;
+      sh_L[qb * 32 + lane] = Ls;
+    }
+  }
+
+  float* sh_o = reinterpret_cast<float*>(smem);        // [4][32][kORedStride]
+  const int rn = tid >> 3;                               // query column this thread finalises
+  const int rd0 = (tid & 7) * (D / 8);                   // first of its D/8 dims
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    if (qb >= nqb) break;
+    __syncthreads();
+#pragma unroll
+    for (int db = 0; db < C::kDBlocks; ++db) {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        float4 v;
+        v.x = oacc[qb][db][4 * r4 + 0] * fscale[qb];
+        v.y = oacc[qb][db][4 * r4 + 1] * fscale[qb];
+        v.z = oacc[qb][db][4 * r4 + 2] * fscale[qb];
+        v.w = oacc[qb][db][4 * r4 + 3] * fscale[qb];
+        const int d = 32 * db + 8 * r4 + 4 * lh;
+        *reinterpret_cast<float4*>(sh_o + (wave * 32 + ln) * C::kORedStride + d) = v;
+      }
+    }
+    __syncthreads();
+    const int row = row0 + 32 * qb + rn;
+    if (row < R) {
+      float acc[D / 8];
+#pragma unroll
+      for (int i = 0; i < D / 8; ++i) acc[i] = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w)
+#pragma unroll
+        for (int i = 0; i < D / 8; i += 4) {
+          const float4 v = *reinterpret_cast<const float4*>(sh_o + (w * 32 + rn) * C::kORedStride + rd0 + i);
+          acc[i] += v.x; acc[i + 1] += v.y; acc[i + 2] += v.z; acc[i + 3] += v.w;
+        }
+      const int node = row / P.G, g = row % P.G;
+      const int64_t grow = static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + g;
+      const float M = sh_M[qb * 32 + rn], Ls = sh_L[qb * 32 + rn];
+      if (nchunks == 1) {
+        const float inv = 1.f / Ls;
+        if (P.out_f32) {
+          float* o = static_cast<float*>(P.out) + grow * D + rd0;
+#pragma unroll
+          for (int i = 0; i < D / 8; ++i) o[i] = acc[i] * inv;
+        } else {
+          uint32_t* o = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(P.out) + grow * D + rd0);
+#pragma unroll
+          for (int i = 0; i < D / 16; ++i) o[i] = pack_bf16(acc[2 * i] * inv, acc[2 * i + 1] * inv);
+        }
+        if (P.lse && (tid & 7) == 0) P.lse[grow] = (M + log2f(Ls)) * static_cast<float>(kLn2);
+      } else {
+        float* o = P.ws_o + (grow * P.max_chunks + chunk) * D + rd0;
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) o[i] = acc[i];
+        if ((tid & 7) == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(M, Ls);
+      }
+    }
+  }
+}
+
+// Merge the per-chunk partials of every (query row, head) that spans several chunks.
+template <int D>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P, int total_rows) {
+  constexpr int kPer = D / 32;
+  const int64_t grow = static_cast<int64_t>(blockIdx.x) * 8 + (threadIdx.x >> 5);
+  if (grow >= total_rows) return;
+  const int d0 = (threadIdx.x & 31) * kPer;
+  const int qi = static_cast<int>(grow / P.Hq);
+  // request that owns query row qi (q_offsets is sorted)
+  int lo = 0, hi = P.B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (P.q_offsets[mid] <= qi) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  int n = P.q_offsets[b + 1] - P.q_offsets[b];
+  n = n > kMaxQ ? kMaxQ : n;
+  if (qi - P.q_offsets[b] >= n) return;
+  const int L = P.ctx_len[b] + n;
+  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+  if (nchunks == 1) return;
+  float M = -INFINITY;
+  for (int c = 0; c < nchunks; ++c) M = fmaxf(M, P.ws_ml[grow * P.max_chunks + c].x);
+  float acc[kPer];
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) acc[i] = 0.f;
+  float W = 0.f;
+  for (int c = 0; c < nchunks; ++c) {
+    const float2 ml = P.ws_ml[grow * P.max_chunks + c];
+    if (ml.x == -INFINITY) continue;
+    const float f = fast_exp2(ml.x - M);
+    W += ml.y * f;
+    const float* o = P.ws_o + (grow * P.max_chunks + c) * D + d0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) acc[i] += o[i] * f;
+  }
+  const float inv = 1.f / W;
+  if (P.out_f32) {
+    float* o = static_cast<float*>(P.out) + grow * D + d0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) o[i] = acc[i] * inv;
+  } else {
+    uint16_t* o = static_cast<uint16_t*>(P.out) + grow * D + d0;
+#pragma unroll
+    for (int i = 0; i < kPer; i += 2) *reinterpret_cast<uint32_t*>(o + i) = pack_bf16(acc[i] * inv, acc[i + 1] * inv);
+  }
+  if (P.lse && (threadIdx.x & 31) == 0) P.lse[grow] = (M + log2f(W)) * static_cast<float>(kLn2);
+}
+
+// ----------------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------------
+struct AttnPlan {
+  int nqb;            // query blocks per workgroup (template instance)
+  int row_groups;
+  int chunk_tokens;
+  int max_chunks;
+};
+
+static AttnPlan make_plan(const AttnArgs& a) {
+  AttnPlan p;
+  const int G = a.Hq / a.Hkv;
+  const int max_rows = a.max_q * G;
+  p.nqb = max_rows <= 32 ? 1 : (max_rows <= 64 ? 2 : 4);
+  p.row_groups = (max_rows + 32 * p.nqb - 1) / (32 * p.nqb);
+  const int64_t max_tok = static_cast<int64_t>(a.max_pages) * a.page;
+  int64_t tok = a.kv_hint > 0 ? a.kv_hint : static_cast<int64_t>(a.B) * max_tok;
+  // aim at ~4 workgroups per compute unit so that the dispatcher can balance ragged lengths
+  const int64_t jobs_target = 1024;
+  int64_t chunk = (tok * a.Hkv * p.row_groups + jobs_target - 1) / jobs_target;
+  if (chunk < 256) chunk = 256;
+  chunk = (chunk + kTile - 1) / kTile * kTile;
+  if (chunk > max_tok) chunk = (max_tok + kTile - 1) / kTile * kTile;
+  if (chunk < kTile) chunk = kTile;
+  p.chunk_tokens = static_cast<int>(chunk);
+  p.max_chunks = static_cast<int>((max_tok + chunk - 1) / chunk);
+  if (p.max_chunks < 1) p.max_chunks = 1;
+  return p;
+}
+
+size_t attn_workspace_bytes(const AttnArgs& a) {
+  const AttnPlan p = make_plan(a);
+  if (p.max_chunks <= 1) return 256;
+  const size_t rows = static_cast<size_t>(a.total_q) * a.Hq;
+  return rows * p.max_chunks * (a.D + 2) * sizeof(float) + 256;
+}
+
+template <int D, int NQB>
+static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
+  using C = AttnCfg<D>;
+  constexpr size_t kMerge = kAttnWaves * 32 * C::kORedStride * sizeof(float) + (2 * kAttnWaves + 2) * NQB * 32 * sizeof(float);
+  constexpr size_t kTiles = static_cast<size_t>(kAttnWaves) * C::kWaveLds;
+  static_assert(kMerge <= kTiles, "merge buffers must fit in the tile memory");
+  const size_t lds = kTiles;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_stream_kernel<D, NQB>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+      return -6;
+    attr_done = true;
+  }
+  dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
+  hipLaunchKernelGGL((attn_stream_kernel<D, NQB>), grid, dim3(kAttnThreads), lds, stream, P);
+  return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+int launch_attn(const AttnArgs& a, hipStream_t stream) {
+  if (a.B <= 0 || a.total_q <= 0) return 0;
+  const AttnPlan plan = make_plan(a);
+  AttnParams P;
+  P.q = static_cast<const uint16_t*>(a.q);
+  P.k_pool = static_cast<const uint16_t*>(a.k_pool);
+  P.v_pool = static_cast<const uint16_t*>(a.v_pool);
+  P.block_table = a.block_table; P.ctx_len = a.ctx_len; P.q_offsets = a.q_offsets; P.parent = a.parent;
+  P.out = a.out; P.lse = a.lse;
+  const size_t rows = static_cast<size_t>(a.total_q) * a.Hq;
+  P.ws_ml = static_cast<float2*>(a.workspace);
+  P.ws_o = reinterpret_cast<float*>(static_cast<unsigned char*>(a.workspace) +
+                                    ((rows * plan.max_chunks * sizeof(float2) + 255) / 256) * 256);
+  P.B = a.B; P.Hq = a.Hq; P.Hkv = a.Hkv; P.G = a.Hq / a.Hkv; P.max_pages = a.max_pages;
+  P.chunk_tokens = plan.chunk_tokens; P.max_chunks = plan.max_chunks;
+  P.c = a.scale * kLog2e;
+  P.out_f32 = (a.out_dtype == kF32);
+  int rc;
+  if (a.D == 128) {
+    if (plan.nqb == 1) rc = launch_stream<128, 1>(P, plan, a.B, a.Hkv, stream);
+    else if (plan.nqb == 2) rc = launch_stream<128, 2>(P, plan, a.B, a.Hkv, stream);
+    else rc = launch_stream<128, 4>(P, plan, a.B, a.Hkv, stream);
+  } else {
+    if (plan.nqb == 1) rc = launch_stream<64, 1>(P, plan, a.B, a.Hkv, stream);
+    else if (plan.nqb == 2) rc = launch_stream<64, 2>(P, plan, a.B, a.Hkv, stream);
+    else rc = launch_stream<64, 4>(P, plan, a.B, a.Hkv, stream);
+  }
+  if (rc != 0) return rc;
+  if (plan.max_chunks > 1) {
+    const int total_rows = static_cast<int>(rows);
+    dim3 grid((total_rows + 7) / 8);
+    if (a.D == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, grid, dim3(256), 0, stream, P, total_rows);
+    else hipLaunchKernelGGL(attn_combine_kernel<64>, grid, dim3(256), 0, stream, P, total_rows);
+    if (hipGetLastError() != hipSuccess) return -6;
+  }
+  return 0;
+}
+
+}  // namespace specv

@@ -1,0 +1,82 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header
+declares, and rejects bad host-visible arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_10325_amd import binding as sv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spec_verify.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(sv.LIB_PATH), reason="libspecverify.so not built")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(spec_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(sv.EXPORTS)
+    L = ctypes.CDLL(sv.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert sv.lib().spec_abi_version() == 1
+    assert sv.strerror(0) == "ok" and "workspace" in sv.strerror(-4)
+
+
+def test_attn_descriptor_validation_needs_no_gpu():
+    L = sv.lib()
+    null = ctypes.c_void_p(0)
+
+    def call(desc):
+        return L.spec_verify_attn(ctypes.byref(desc), null, null, null, null, null, null, null, null, null,
+                                  null, 0, null)
+
+    ok = dict(batch=2, num_q_heads=8, num_kv_heads=2, head_dim=128, total_q=8, max_q_per_req=4,
+              max_pages_per_req=10)
+    assert call(sv.make_attn_desc(**ok)) == -1                                   # NULL tensors
+    assert call(sv.make_attn_desc(**{**ok, "num_kv_heads": 3})) == -2            # Hq % Hkv
+    assert call(sv.make_attn_desc(**{**ok, "head_dim": 96})) == -3
+    assert call(sv.make_attn_desc(**{**ok, "page_size": 32})) == -3
+    assert call(sv.make_attn_desc(**{**ok, "max_q_per_req": 65})) == -3
+    assert call(sv.make_attn_desc(**{**ok, "batch": -1})) == -2
+    assert call(sv.make_attn_desc(**{**ok, "batch": 0})) == 0                    # empty batch: nothing to do
+    assert L.spec_verify_attn(None, null, null, null, null, null, null, null, null, null, null, 0, null) == -1
+    assert sv.spec_verify_attn_workspace_size(sv.make_attn_desc(**ok)) >= 256
+    assert sv.spec_verify_attn_workspace_size(sv.make_attn_desc(**{**ok, "head_dim": 96})) == 0
+
+
+def test_accept_and_fuse_validation_needs_no_gpu():
+    L = sv.lib()
+    null = ctypes.c_void_p(0)
+
+    def accept(B=2, V=100, total=4, nq=4, maxn=2, T=1.0, stride=3, tdt=0, qdt=0, qk=0):
+        return L.spec_accept(B, V, total, nq, maxn, null, null, null, null, tdt, null, qdt, qk, null, T,
+                             null, null, null, null, stride, null, null, null, 0, null)
+
+    assert accept() == -1
+    assert accept(V=0) == -2
+    assert accept(T=0.0) == -2
+    assert accept(maxn=65, stride=66) == -3
+    assert accept(stride=2) == -2
+    assert accept(tdt=7) == -3
+    assert accept(qk=2) == -3
+    assert accept(B=0) == 0
+    assert sv.spec_accept_workspace_size(2, 4, 4, 100) > 0
+
+    def fuse(B=2, k=3, N=4, V=100, mode=0, T=1.0):
+        return L.spec_fuse_drafts(B, k, N, V, null, null, null, null, 0, T, mode, null, null, null, null,
+                                  null, 0, null)
+
+    assert fuse() == -1
+    assert fuse(N=0) == -2
+    assert fuse(mode=5) == -3
+    assert fuse(B=0) == 0
+    assert sv.spec_fuse_drafts_workspace_size(2, 3, 4, 100, 0) == 0
+    assert sv.spec_fuse_drafts_workspace_size(2, 3, 4, 100, 1) > 0

@@ -1,0 +1,227 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element, on seeded inputs whose sizes span several tiles, chunks and ragged tails."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2503_10325_amd import workloads as W
+
+from gpu_util import ATTN_TOL, attn_rel_err, compare_accept, oracle_attn, ratio_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2503_10325_amd import binding, runner
+    binding.lib()                      # fail loudly when the HIP library is missing
+    return runner
+
+
+C = W.CONFIGS
+ATTN_CASES = {
+    "tiny_full": C["c0_tiny"],
+    "linear_mha_d128": W.scaled(C["c1_llama2_7b"], batch=3, n_q_heads=4, n_kv_heads=4, ctx=("fixed", 333)),
+    "linear_multi_chunk": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=2, ctx=("fixed", 1500)),
+    "tree64_gqa4": W.scaled(C["c2_tree_llama3_8b"], batch=2, n_q_heads=8, n_kv_heads=2, ctx=("fixed", 210)),
+    "tree_small_gqa": W.scaled(C["c2_tree_llama3_8b"], batch=3, n_q_heads=4, n_kv_heads=2, ctx=("uniform", 1, 90),
+                               draft=("tree", (3, 2, 2), 17)),
+    "ragged_gqa8": W.scaled(C["c4_llama70b_serving"], batch=7, n_q_heads=16, n_kv_heads=2,
+                            ctx=("lognormal", 300, 0.8, 17, 1500)),
+    "d64_gqa2": W.scaled(C["c0_tiny"], batch=3, n_q_heads=4, n_kv_heads=2, ctx=("uniform", 5, 400),
+                         draft=("linear_uniform", 1, 9)),
+    "ctx_zero": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=1, ctx=("fixed", 0), draft=("linear", 5)),
+    "page_boundary": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=2, ctx=("fixed", 56), draft=("linear", 8)),
+}
+
+
+@pytest.mark.parametrize("name", list(ATTN_CASES))
+def test_attention_matches_oracle(rt, name):
+    cfg = ATTN_CASES[name]
+    a = W.make_attn_inputs(cfg, seed=11)
+    ref, ref_lse = oracle_attn(a)
+    dev = rt.DeviceAttn(a)
+    dev.run()
+    torch.cuda.synchronize()
+    got = dev.out.float().cpu().numpy()
+    err = attn_rel_err(got, ref)
+    assert np.isfinite(got).all()
+    assert err <= ATTN_TOL, f"{name}: rel err {err}"
+    lse = dev.lse.cpu().numpy()
+    assert np.abs(lse - ref_lse).max() < 2e-2, f"{name}: lse err {np.abs(lse - ref_lse).max()}"
+
+
+def test_attention_fp32_output_and_determinism(rt):
+    cfg = ATTN_CASES["ragged_gqa8"]
+    a = W.make_attn_inputs(cfg, seed=5)
+    ref, _ = oracle_attn(a)
+    dev = rt.DeviceAttn(a, out_dtype=torch.float32)
+    dev.run()
+    torch.cuda.synchronize()
+    first = dev.out.clone()
+    assert attn_rel_err(first.cpu().numpy(), ref) <= ATTN_TOL
+    dev.workspace.fill_(0xFF)                     # poisoned workspace must not leak into results
+    dev.out.zero_()
+    dev.run()
+    torch.cuda.synchronize()
+    assert torch.equal(first, dev.out)            # bit-identical from run to run
+
+
+def test_attention_ignores_stale_cache_slots(rt):
+    """Slots past ctx+n in the last page and unused pool pages may hold anything (NaN here)."""
+    cfg = W.scaled(C["c1_llama2_7b"], batch=3, n_q_heads=4, n_kv_heads=2, ctx=("uniform", 20, 200), draft=("linear", 3))
+    a = W.make_attn_inputs(cfg, seed=2)
+    ref, _ = oracle_attn(a)
+    nan_bits = np.uint16(0x7FC0)
+    used = np.zeros(a.num_pages, dtype=bool)
+    for b in range(cfg.batch):
+        L = int(a.st.ctx_len[b] + a.st.n[b])
+        npg = (L + 15) // 16
+        used[a.block_table[b, :npg]] = True
+        if L % 16:
+            pg = a.block_table[b, npg - 1]
+            a.k_pool[pg, :, L % 16:, :] = nan_bits
+            a.v_pool[pg, :, L % 16:, :] = nan_bits
+    a.k_pool[~used] = nan_bits
+    a.v_pool[~used] = nan_bits
+    dev = rt.DeviceAttn(a)
+    dev.run()
+    torch.cuda.synchronize()
+    got = dev.out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    assert attn_rel_err(got, ref) <= ATTN_TOL
+
+
+def test_attention_empty_request_in_batch(rt):
+    cfg = W.scaled(C["c1_llama2_7b"], batch=3, n_q_heads=2, n_kv_heads=2, ctx=("fixed", 100), draft=("linear", 4))
+    st = W.make_structure(cfg, seed=1)
+    st.n[1] = 0
+    st.node_offsets[1:] = np.cumsum(st.n)
+    a = W.make_attn_inputs(cfg, seed=1, st=st)
+    ref, _ = oracle_attn(a)
+    dev = rt.DeviceAttn(a)
+    dev.run()
+    torch.cuda.synchronize()
+    assert attn_rel_err(dev.out.float().cpu().numpy(), ref) <= ATTN_TOL
+
+
+# --------------------------------------------------------------------------------
+ACCEPT_CASES = {
+    "tiny_full": (C["c0_tiny"], {}),
+    "linear_v32000": (W.scaled(C["c1_llama2_7b"], batch=6), {}),
+    "linear_odd_vocab": (W.scaled(C["c1_llama2_7b"], batch=9, vocab=1001, draft=("linear_uniform", 1, 7)), {}),
+    "tree_v20000": (W.scaled(C["c2_tree_llama3_8b"], batch=5, vocab=20000), {}),
+    "tree_wide": (W.scaled(C["c2_tree_llama3_8b"], batch=12, vocab=3000, draft=("tree", (5, 3), 20),
+                           q_src=("noise", 2.0)), {}),
+    "ragged_big_vocab": (W.scaled(C["c4_llama70b_serving"], batch=5), {}),
+    "fp32_logits": (W.scaled(C["c1_llama2_7b"], batch=8, vocab=5000), {"fp32": True}),
+    "temperature": (W.scaled(C["c1_llama2_7b"], batch=8, vocab=4096, temperature=0.7), {"fp32": True}),
+}
+
+
+def _run_accept(rt, cfg, ai, fp32=False, q_kind=0, draft_q=None):
+    tl, dq = ai.target_logits, (ai.draft_q if draft_q is None else draft_q)
+    if fp32:
+        tl = W.bf16_bits_to_f32(tl)
+        if dq.dtype == np.uint16:
+            dq = W.bf16_bits_to_f32(dq)
+    ref = oracle.accept(ai.st.node_offsets, ai.st.parent, ai.draft_tokens, tl, dq, ai.q_row, ai.u_accept,
+                        ai.u_resample, temperature=cfg.temperature, qkind=q_kind)
+    dev = rt.DeviceAccept(ai.st, tl, dq, ai.q_row, ai.draft_tokens, ai.u_accept, ai.u_resample,
+                          temperature=cfg.temperature, q_kind=q_kind)
+    dev.run()
+    return dev.results(), ref
+
+
+@pytest.mark.parametrize("name", list(ACCEPT_CASES))
+def test_accept_matches_oracle(rt, name):
+    cfg, opt = ACCEPT_CASES[name]
+    ai = W.make_accept_inputs(cfg, seed=4)
+    got, ref = _run_accept(rt, cfg, ai, fp32=opt.get("fp32", False))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    print(f"{name}: near-ties {ties}/{B}, mean accept_len {ref['accept_len'].mean():.2f}")
+    assert not bad, f"{name}: requests {bad} differ outside near-ties"
+    assert ties <= max(1, B // 4)
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+    assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
+
+
+def test_accept_draft_equals_target_accepts_all(rt):
+    cfg = W.scaled(C["c1_llama2_7b"], batch=5, vocab=8000)
+    ai = W.make_accept_inputs(cfg, seed=9, draft_equals_target=True)
+    got, ref = _run_accept(rt, cfg, ai)
+    assert np.array_equal(got["accept_len"], ai.st.n)
+    bad, ties, _ = compare_accept(got, ref, ai.st.n)
+    assert not bad
+
+
+def test_accept_with_probability_rows(rt):
+    """Draft rows given as probabilities (as the MIXTURE fusion produces them)."""
+    cfg = W.scaled(C["c1_llama2_7b"], batch=6, vocab=2048)
+    ai = W.make_accept_inputs(cfg, seed=6)
+    z = W.bf16_bits_to_f32(ai.draft_q).astype(np.float64)
+    e = np.exp(z - z.max(-1, keepdims=True))
+    probs = (e / e.sum(-1, keepdims=True)).astype(np.float32)
+    got, ref = _run_accept(rt, cfg, ai, q_kind=1, draft_q=probs)
+    bad, ties, _ = compare_accept(got, ref, ai.st.n)
+    assert not bad
+
+
+def test_accept_zero_nodes_request(rt):
+    cfg = W.scaled(C["c1_llama2_7b"], batch=4, vocab=1000, draft=("linear", 3))
+    st = W.make_structure(cfg, seed=2)
+    st.n[2] = 0
+    st.node_offsets[1:] = np.cumsum(st.n)
+    ai = W.make_accept_inputs(cfg, seed=2, st=st)
+    got, ref = _run_accept(rt, cfg, ai)
+    bad, ties, _ = compare_accept(got, ref, st.n)
+    assert not bad and got["accept_len"][2] == 0
+
+
+# --------------------------------------------------------------------------------
+def test_fusion_argmax_and_mixture_match_oracle(rt):
+    from paper_2503_10325_amd import binding as sv
+    cfg = W.scaled(C["c3_fusion"], batch=4, vocab=3000)
+    ai = W.make_accept_inputs(cfg, seed=8)
+    f = ai.fusion
+    f.k_len = np.array([6, 5, 6, 1], dtype=np.int32)
+    f.conf[0, 2, :] = 0.5                                  # a tie: lowest drafter index wins
+    ref = oracle.fuse_drafts(f.k_len, f.conf, f.draft_tokens)
+    dev = rt.DeviceFuse(f, cfg.vocab)
+    dev.run()
+    torch.cuda.synchronize()
+    for key, t in (("fused_token", dev.fused_token), ("winner", dev.winner), ("q_row", dev.q_row)):
+        assert np.array_equal(t.cpu().numpy(), ref[key]), key
+    T = 1.3
+    refm = oracle.fuse_drafts(f.k_len, f.conf, f.draft_tokens, f.draft_logits, temperature=T,
+                              mode=oracle.FUSE_MIXTURE)
+    devm = rt.DeviceFuse(f, cfg.vocab, temperature=T, mode=sv.SPEC_FUSE_MIXTURE)
+    devm.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(devm.q_row.cpu().numpy(), refm["q_row"])
+    got = devm.fused_probs.cpu().numpy().astype(np.float64)
+    valid = (np.arange(6)[None, :] < f.k_len[:, None]).reshape(-1)
+    err = np.abs(got[valid] - refm["fused_probs"][valid]) / (refm["fused_probs"][valid] + 1e-12)
+    assert err.max() < 2e-5, err.max()
+    assert np.abs(got[valid].sum(-1) - 1).max() < 1e-5
+
+
+def test_fusion_then_accept_pipeline(rt):
+    """Config-3 style: ARGMAX fusion output feeds the acceptance step on the device."""
+    cfg = W.scaled(C["c3_fusion"], batch=5, vocab=4000)
+    ai = W.make_accept_inputs(cfg, seed=12)
+    f = ai.fusion
+    rf = oracle.fuse_drafts(f.k_len, f.conf, f.draft_tokens)
+    ref = oracle.accept(ai.st.node_offsets, None, rf["fused_token"].reshape(-1), ai.target_logits, f.draft_logits,
+                        rf["q_row"].reshape(-1), ai.u_accept, ai.u_resample)
+    dev = rt.DeviceFuse(f, cfg.vocab)
+    dev.run()
+    acc = rt.DeviceAccept(ai.st, ai.target_logits, dev.draft_logits, dev.q_row.view(-1), dev.fused_token.view(-1),
+                          ai.u_accept, ai.u_resample)
+    acc.run()
+    bad, ties, _ = compare_accept(acc.results(), ref, ai.st.n)
+    assert not bad
