@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the parallel-verification hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch: spec_verify_attn,
+spec_fuse_drafts and spec_accept enqueued on one stream.  Inputs are resident in
+HBM before the timed region; several independent copies of every input are rotated
+so that no step finds its data in the last-level cache.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "verified draft tokens/sec + achieved HBM GB/s (verify-attn+accept), 1 MI355X"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c1_llama2_7b")
+    ap.add_argument("--copies", type=int, default=4, help="independent input copies rotated per step")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
+    return ap.parse_args()
+
+
+def read_traffic(workload):
+    """HBM bytes per attention launch derived from rocprofv3 --pmc runs, if recorded."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+class Step:
+    """Device state of one input copy and the three calls of one step."""
+
+    def __init__(self, cfg, a, ai, runner, sv):
+        import torch
+        self.attn = runner.DeviceAttn(a, want_lse=False)
+        st = a.st
+        if ai.fusion is not None:
+            self.fuse = runner.DeviceFuse(ai.fusion, cfg.vocab, temperature=cfg.temperature)
+            assert int(st.n.min()) == int(st.n.max()), "fusion output is used as a flat [B*k] view"
+            self.accept = runner.DeviceAccept(st, ai.target_logits, self.fuse.draft_logits,
+                                              self.fuse.q_row.view(-1), self.fuse.fused_token.view(-1),
+                                              ai.u_accept, ai.u_resample, temperature=cfg.temperature,
+                                              want_debug=False)
+        else:
+            # single drafter: the fusion step degenerates to N = 1 (identity) but still runs
+            B, k_max = cfg.batch, int(st.n.max())
+            from paper_2503_10325_amd import workloads as W
+            conf = np.ones((B, k_max, 1), dtype=np.float32)
+            toks = np.zeros((B, k_max, 1), dtype=np.int32)
+            for b in range(B):
+                o, k = int(st.node_offsets[b]), int(st.n[b])
+                toks[b, :k, 0] = ai.draft_tokens[o:o + k]
+            f = W.FusionInputs(1, k_max, st.n.astype(np.int32), conf, toks, None)
+            self.fuse = runner.DeviceFuse(f, cfg.vocab, temperature=cfg.temperature,
+                                          draft_logits_dev=torch.empty(0, device="cuda"))
+            self.fuse.draft_logits = None
+            uniform = int(st.n.min()) == int(st.n.max())
+            # with a uniform draft length the fused [B, k] outputs are the flat node arrays
+            self.accept = runner.DeviceAccept(st, ai.target_logits, ai.draft_q,
+                                              self.fuse.q_row.view(-1) if uniform else ai.q_row,
+                                              self.fuse.fused_token.view(-1) if uniform else ai.draft_tokens,
+                                              ai.u_accept, ai.u_resample, temperature=cfg.temperature,
+                                              want_debug=False)
+
+    def run(self, ev0=None, ev1=None):
+        if ev0 is not None:
+            ev0.record()
+        self.attn.run()
+        if ev1 is not None:
+            ev1.record()
+        self.fuse.run()
+        self.accept.run()
+
+
+def cpu_baseline(cfg, a, ai, budget_s):
+    """The oracle, as it stands, timed on the host cores over whole batches of the workload."""
+    import oracle
+    reps, t_total = 0, 0.0
+    tokens = int(a.st.total)
+    while reps < 1 or (t_total < budget_s and reps < 50):
+        t0 = time.perf_counter()
+        oracle.verify_attn(a.q, a.k_pool, a.v_pool, a.block_table, a.st.ctx_len, a.st.node_offsets,
+                           a.st.parent, want_lse=False)
+        if ai.fusion is not None:
+            rf = oracle.fuse_drafts(ai.fusion.k_len, ai.fusion.conf, ai.fusion.draft_tokens)
+            toks, qrow, dq = rf["fused_token"].reshape(-1), rf["q_row"].reshape(-1), ai.fusion.draft_logits
+        else:
+            toks, qrow, dq = ai.draft_tokens, ai.q_row, ai.draft_q
+        oracle.accept(a.st.node_offsets, a.st.parent, toks, ai.target_logits, dq, qrow, ai.u_accept,
+                      ai.u_resample, temperature=cfg.temperature)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    return dict(value=tokens * reps / t_total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{reps} pass(es) over the full {cfg.name} batch ({tokens} draft tokens each), "
+                       f"{t_total:.2f} s of oracle time")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2503_10325_amd import binding as sv
+    from paper_2503_10325_amd import runner
+    from paper_2503_10325_amd import workloads as W
+    sv.lib()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    cfg = W.CONFIGS[args.workload]
+    a = W.make_attn_inputs(cfg, seed=args.seed)
+    ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
+    copies = [Step(cfg, a, ai, runner, sv) for _ in range(max(1, args.copies))]
+    torch.cuda.synchronize()
+
+    for i in range(args.warmup):
+        copies[i % len(copies)].run()
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        copies[i % len(copies)].run(ev[i][0], ev[i][1])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    attn_ms = np.array([e0.elapsed_time(e1) for e0, e1 in ev])
+    attn_s = float(attn_ms.mean()) * 1e-3
+    tokens = int(a.st.total)
+    attn_bytes, attn_flops = W.attention_bytes_flops(cfg, a.st)
+    n_logit_rows = ai.target_logits.shape[0] + (ai.fusion.draft_logits.shape[0] if ai.fusion else ai.draft_q.shape[0])
+    accept_bytes = n_logit_rows * cfg.vocab * 2
+    achieved = attn_bytes / attn_s / 1e9
+    out = {
+        "metric": METRIC,
+        "value": tokens * args.steps / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "draft_tokens_per_step": tokens,
+                   "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
+                   "context": str(cfg.ctx), "draft": str(cfg.draft), "vocab": cfg.vocab,
+                   "input_copies_rotated": len(copies)},
+        "step_hbm_gbs": (attn_bytes + accept_bytes) / (elapsed / args.steps) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn (attn_stream_kernel + chunk combine)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic(cfg.name), "algorithmic_bytes": attn_bytes,
+                     "launch_us_mean": attn_s * 1e6, "launch_us_p10": float(np.percentile(attn_ms, 10)) * 1e3,
+                     "launch_us_p90": float(np.percentile(attn_ms, 90)) * 1e3,
+                     "mfma_tflops": attn_flops / attn_s / 1e12},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
