@@ -192,23 +192,60 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   __shared__ double sh_wave_sum[kWalkWaves];
   __shared__ double sh_inv_R[kMaxNodes];
   __shared__ int sh_token;
+  // per-request tables filled once, in parallel, so that the walk itself touches no global memory
+  __shared__ float sh_tm[kMaxNodes + 1];       // target local row i: max logit
+  __shared__ double sh_tinvz[kMaxNodes + 1];   //                     1 / sum 2^((l-m)c)
+  __shared__ float sh_qm[kMaxNodes];           // draft row of node j
+  __shared__ double sh_qinvz[kMaxNodes];
+  __shared__ int sh_par[kMaxNodes], sh_tok[kMaxNodes], sh_qrow[kMaxNodes];
+  __shared__ double sh_px[kMaxNodes], sh_qx[kMaxNodes];   // p_parent(x_j), q(x_j)
+  __shared__ float sh_u[kMaxNodes];
 
-  if (P.dbg_ratio) {
-    for (int i = tid; i < n; i += kWalkThreads) P.dbg_ratio[o + i] = __builtin_nanf("");
-    __syncthreads();               // thread 0 overwrites visited entries later
+  const bool q_is_probs = (P.q_kind == 1);
+  if (wave == 0) {
+    if (lane <= n) {
+      const RowStat ps = merge_stats(P.stats, trow0 + lane, P.nseg, c);
+      sh_tm[lane] = ps.m;
+      sh_tinvz[lane] = 1.0 / ps.z;
+    }
+  } else if (wave == 1) {
+    if (lane < n) {
+      int par = P.parent ? P.parent[o + lane] : lane - 1;
+      if (par < -1 || par >= lane) par = -1;
+      const int qr = P.q_row[o + lane];
+      sh_par[lane] = par;
+      sh_tok[lane] = P.draft_tokens[o + lane];
+      sh_qrow[lane] = qr;
+      sh_u[lane] = P.u_accept[o + lane];
+      if (!q_is_probs) {
+        const RowStat qs = merge_stats(P.stats, static_cast<int64_t>(P.n_t_rows) + qr, P.nseg, c);
+        sh_qm[lane] = qs.m;
+        sh_qinvz[lane] = 1.0 / qs.z;
+      }
+      if (P.dbg_ratio) P.dbg_ratio[o + lane] = __builtin_nanf("");
+    }
   }
+  __syncthreads();
+  if (tid < n) {
+    const int x = sh_tok[tid], par = sh_par[tid];
+    const int64_t prow = trow0 + 1 + par;
+    const double lp = static_cast<double>(load_logit(P.target, P.t_dtype, prow * V + x));
+    sh_px[tid] = exp2((lp - static_cast<double>(sh_tm[par + 1])) * static_cast<double>(c)) * sh_tinvz[par + 1];
+    const int64_t qoff = static_cast<int64_t>(sh_qrow[tid]) * V + x;
+    if (q_is_probs) sh_qx[tid] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, qoff));
+    else {
+      const double lq = static_cast<double>(load_logit(P.draft_q, P.q_dtype, qoff));
+      sh_qx[tid] = exp2((lq - static_cast<double>(sh_qm[tid])) * static_cast<double>(c)) * sh_qinvz[tid];
+    }
+  }
+  __syncthreads();
 
-  // this lane's node (lanes >= n hold an impossible parent)
-  int my_parent = -2;
-  if (lane < n) {
-    my_parent = P.parent ? P.parent[o + lane] : lane - 1;
-    if (my_parent < -1 || my_parent >= lane) my_parent = -1;
-  }
+  const int my_parent = (lane < n) ? sh_par[lane] : -2;   // lanes >= n hold an impossible parent
 
   int cur = -1, depth = 0;
   WalkRows R;
   R.t_base = P.target; R.t_dtype = P.t_dtype;
-  R.q_base = P.draft_q; R.q_dtype = P.q_dtype; R.q_is_probs = (P.q_kind == 1);
+  R.q_base = P.draft_q; R.q_dtype = P.q_dtype; R.q_is_probs = q_is_probs;
   R.q_off = 0; R.q_m = 0.f; R.q_invz = 0.0; R.have_q = 0;
 
   // one full pass at residual level L: per-wave sums to LDS, returns the total
@@ -237,11 +274,9 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
 
   for (int guard = 0; guard <= kMaxNodes; ++guard) {
     // target row of the current node
-    const int64_t prow = trow0 + 1 + cur;
-    const RowStat ps = merge_stats(P.stats, prow, P.nseg, c);
-    R.t_off = prow * static_cast<int64_t>(V);
-    R.t_m = ps.m;
-    R.t_invz = 1.0 / ps.z;
+    R.t_off = (trow0 + 1 + cur) * static_cast<int64_t>(V);
+    R.t_m = sh_tm[cur + 1];
+    R.t_invz = sh_tinvz[cur + 1];
     level = 0;
     sums_level = -1;
     R.have_q = 0;
@@ -251,27 +286,14 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     while (kids) {
       const int ch = __ffsll(static_cast<long long>(kids)) - 1;
       kids &= kids - 1;
-      const int x = P.draft_tokens[o + ch];
       if (!R.have_q) {
-        const int64_t qr = P.q_row[o + ch];
-        R.q_off = qr * static_cast<int64_t>(V);
-        if (!R.q_is_probs) {
-          const RowStat qs = merge_stats(P.stats, P.n_t_rows + qr, P.nseg, c);
-          R.q_m = qs.m;
-          R.q_invz = 1.0 / qs.z;
-        }
+        R.q_off = static_cast<int64_t>(sh_qrow[ch]) * V;
+        R.q_m = sh_qm[ch];
+        R.q_invz = sh_qinvz[ch];
         R.have_q = 1;
       }
-      // r(x) and q(x), scalar, in fp64
-      const double lp = static_cast<double>(load_logit(P.target, P.t_dtype, R.t_off + x));
-      const double px = exp2((lp - static_cast<double>(R.t_m)) * static_cast<double>(c)) * R.t_invz;
-      double qx;
-      if (R.q_is_probs) qx = static_cast<double>(load_logit(P.draft_q, P.q_dtype, R.q_off + x));
-      else {
-        const double lq = static_cast<double>(load_logit(P.draft_q, P.q_dtype, R.q_off + x));
-        qx = exp2((lq - static_cast<double>(R.q_m)) * static_cast<double>(c)) * R.q_invz;
-      }
-      double rx = px;
+      const double qx = sh_qx[ch];
+      double rx = sh_px[ch];
       for (int k = 0; k < level; ++k) {
         double w = rx - qx;
         w = w > 0.0 ? w : 0.0;
@@ -281,7 +303,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       if (qx > 0.0) ratio = rx / qx;
       else ratio = (rx > 0.0) ? INFINITY : 0.0;
       if (P.dbg_ratio && tid == 0) P.dbg_ratio[o + ch] = static_cast<float>(ratio);
-      const double u = static_cast<double>(P.u_accept[o + ch]);
+      const double u = static_cast<double>(sh_u[ch]);
       if (u < ratio) { accepted = ch; break; }
       // rejected: mass of max(0, r - q)
       const double mass = full_pass(level + 1);
@@ -297,7 +319,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       }
     }
     if (accepted >= 0) {
-      if (tid == 0 && depth < P.out_stride) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + depth] = P.draft_tokens[o + accepted];
+      if (tid == 0 && depth < P.out_stride) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + depth] = sh_tok[accepted];
       ++depth;
       cur = accepted;
       continue;

@@ -32,6 +32,7 @@ static int check_attn_desc(const spec_attn_desc* d) {
   if (d->max_q_per_req > 64) return SPEC_ERR_UNSUPPORTED;
   if (d->out_dtype != SPEC_BF16 && d->out_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
   if (d->batch > 65535 || d->num_kv_heads > 65535) return SPEC_ERR_UNSUPPORTED;
+  if (!(d->scale >= 0.f)) return SPEC_ERR_SHAPE;
   if (d->batch > 0 && d->total_q > 0 && (d->max_pages_per_req == 0 || d->max_q_per_req == 0))
     return SPEC_ERR_SHAPE;
   return SPEC_OK;

@@ -12,6 +12,8 @@
 // V is transposed on its way into LDS (token pairs packed with v_perm).  The waves'
 // partial results are merged through LDS; when a request spans several chunks the
 // workgroup writes an unnormalised partial and attn_combine_kernel merges the chunks.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -67,21 +69,24 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
-  union { uint4 u; bf16x8 b; } x;
-  x.u = v;
-  return x.b;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ u32x4 zero4() {
+  u32x4 z = {0u, 0u, 0u, 0u};
+  return z;
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  union { __bf16 h[2]; uint32_t u; } x;
-  x.h[0] = static_cast<__bf16>(lo);
-  x.h[1] = static_cast<__bf16>(hi);
-  return x.u;
+  bf16x2 x = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
+  return __builtin_bit_cast(uint32_t, x);
 }
 
 template <int D, int NQB>
-__global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P) {
+__global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_kernel(AttnParams P) {
   using C = AttnCfg<D>;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -157,8 +162,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
     const uint16_t* qp = P.q + (static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + g) * D + 8 * lh;
 #pragma unroll
     for (int ks = 0; ks < C::kQKSteps; ++ks) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (valid) v = *reinterpret_cast<const uint4*>(qp + 16 * ks);
+      u32x4 v = zero4();
+      if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
       qf[qb][ks] = as_bf16x8(v);
     }
   }
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
   const int64_t page_elems = static_cast<int64_t>(P.Hkv) * kPage * D;
   const int64_t head_off = static_cast<int64_t>(kvh) * kPage * D;
 
-  uint4 kr[C::kLoads], vr[C::kLoads];
+  u32x4 kr[C::kLoads], vr[C::kLoads];
 
   auto issue_loads = [&](int t) {
     const int tok0 = t_begin + kTile * t;
@@ -203,9 +208,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
     for (int j = 0; j < C::kLoads; ++j) {
       const int tk = j * C::kTokPerLoad + kt;
       const int page = pg[(j * C::kTokPerLoad) / kPage];
-      uint4 v = make_uint4(0, 0, 0, 0);
+      u32x4 v = zero4();
       if (page >= 0)
-        v = *reinterpret_cast<const uint4*>(P.k_pool + page * page_elems + head_off + (tk % kPage) * D + kc * 8);
+        v = *reinterpret_cast<const u32x4*>(P.k_pool + page * page_elems + head_off + (tk % kPage) * D + kc * 8);
       kr[j] = v;
     }
 #pragma unroll
@@ -215,9 +220,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int slot = 4 * va + i;
-        uint4 v = make_uint4(0, 0, 0, 0);
+        u32x4 v = zero4();
         if (page >= 0 && tok0 + kPage * s + slot < L)      // never multiply stale cache slots into O
-          v = *reinterpret_cast<const uint4*>(P.v_pool + page * page_elems + head_off + slot * D + kc * 8);
+          v = *reinterpret_cast<const u32x4*>(P.v_pool + page * page_elems + head_off + slot * D + kc * 8);
         vr[pi * 4 + i] = v;
       }
     }
@@ -230,16 +235,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
 #pragma unroll
     for (int j = 0; j < C::kLoads; ++j) {
       const int tk = j * C::kTokPerLoad + kt;
-      *reinterpret_cast<uint4*>(k_lds + tk * C::kKStride + kc * 16) = kr[j];
+      *reinterpret_cast<u32x4*>(k_lds + tk * C::kKStride + kc * 16) = kr[j];
     }
 #pragma unroll
     for (int pi = 0; pi < C::kVPageIters; ++pi) {
       const int s = pi * C::kPagesPerLoad + vs_lane;
-      const uint4 a0 = vr[pi * 4 + 0], a1 = vr[pi * 4 + 1], a2 = vr[pi * 4 + 2], a3 = vr[pi * 4 + 3];
-      const uint32_t w0[4] = {a0.x, a0.y, a0.z, a0.w};
-      const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
-      const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
-      const uint32_t w3[4] = {a3.x, a3.y, a3.z, a3.w};
+      const u32x4 w0 = vr[pi * 4 + 0], w1 = vr[pi * 4 + 1], w2 = vr[pi * 4 + 2], w3 = vr[pi * 4 + 3];
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
 #pragma unroll
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
       for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::kQKSteps; ++ks) {
-      const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(k_lds + ln * C::kKStride + 32 * ks + 16 * lh));
+      const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(k_lds + ln * C::kKStride + 32 * ks + 16 * lh));
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb)
         if (qb < nqb) sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[qb], 0, 0, 0);
@@ -302,20 +303,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
         }
         // A single bf16 rounding of P (2^-9 relative) would dominate the output error; carrying
         // the rounding residual in a second bf16 term keeps ~16 bits of every weight.
-        union { uint32_t u[4]; bf16x8 v; } f0, f1, g0, g1;
+        u32x4 f0, f1, g0, g1;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t h0 = pack_bf16(p[2 * j], p[2 * j + 1]);
           const uint32_t h1 = pack_bf16(p[8 + 2 * j], p[8 + 2 * j + 1]);
-          f0.u[j] = h0;
-          f1.u[j] = h1;
-          g0.u[j] = pack_bf16(p[2 * j] - bf16_lo(h0), p[2 * j + 1] - bf16_hi(h0));
-          g1.u[j] = pack_bf16(p[8 + 2 * j] - bf16_lo(h1), p[8 + 2 * j + 1] - bf16_hi(h1));
+          f0[j] = h0;
+          f1[j] = h1;
+          g0[j] = pack_bf16(p[2 * j] - bf16_lo(h0), p[2 * j + 1] - bf16_hi(h0));
+          g1[j] = pack_bf16(p[8 + 2 * j] - bf16_lo(h1), p[8 + 2 * j + 1] - bf16_hi(h1));
         }
-        pf[qb][0] = f0.v;
-        pf[qb][1] = f1.v;
-        pl[qb][0] = g0.v;
-        pl[qb][1] = g1.v;
+        pf[qb][0] = __builtin_bit_cast(bf16x8, f0);
+        pf[qb][1] = __builtin_bit_cast(bf16x8, f1);
+        pl[qb][0] = __builtin_bit_cast(bf16x8, g0);
+        pl[qb][1] = __builtin_bit_cast(bf16x8, g1);
         l_run[qb] = l_run[qb] * alpha + psum;
         m_run[qb] = m_new;
         if (__any(alpha != 1.f)) {
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
       const int vrow = (d & 7) * 18 + (d >> 3);
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
-        const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(v_lds + vrow * C::kVStride + 32 * s + 16 * lh));
+        const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(v_lds + vrow * C::kVStride + 32 * s + 16 * lh));
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb)
           if (qb < nqb) {
@@ -435,6 +436,308 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnParams P)
   }
 }
 
+// ----------------------------------------------------------------------------------
+// Row-split variant for requests with more than 32 query rows per KV head (GQA groups
+// times several drafts, draft trees).  The NW waves of a workgroup stage 64-token tiles
+// cooperatively (double-buffered in LDS) and every wave owns one block of 32 query rows,
+// for which it sees every token: no cross-wave merge is needed.
+// ----------------------------------------------------------------------------------
+template <int D, int NW>
+struct RowsCfg {
+  static constexpr int kT = 64;                            // tokens per tile
+  static constexpr int kThreads = NW * 64;
+  static constexpr int kCh = D / 8;
+  static constexpr int kLoads = kT * kCh / kThreads;       // 16-byte loads per thread per tensor
+  static constexpr int kTpt = kLoads;                      // consecutive tokens a thread transposes
+  static constexpr int kKStride = D * 2 + 16;
+  static constexpr int kKBytes = kT * kKStride;
+  static constexpr int kVStride = kT * 2 + 16;
+  static constexpr int kVRows = 7 * 18 + D / 8;
+  static constexpr int kVBytes = kVRows * kVStride;
+  static constexpr int kStage = kKBytes + kVBytes;
+  static constexpr int kMaxChunkPages = 1024;              // a chunk spans at most 16384 tokens
+  static constexpr int kLds = 2 * kStage + 768 + kMaxChunkPages * 4;
+  static_assert(kTpt == 4 || kTpt == 2, "unsupported tile/thread combination");
+};
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(AttnParams P) {
+  using C = AttnCfg<D>;
+  using RC = RowsCfg<D, NW>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
+
+  const int q0 = P.q_offsets[b];
+  int n = P.q_offsets[b + 1] - q0;
+  n = n > kMaxQ ? kMaxQ : n;
+  if (n <= 0) return;
+  const int ctx = P.ctx_len[b];
+  const int L = ctx + n;
+  const int R = n * P.G;
+  const int row0 = rg * (32 * NW);
+  if (row0 >= R) return;
+  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+  if (chunk >= nchunks) return;
+  const int cb = (((L + nchunks - 1) / nchunks) + RC::kT - 1) & ~(RC::kT - 1);
+  const int t_begin = chunk * cb;
+  if (t_begin >= L) return;                     // rounding the chunk up to whole tiles can empty the last one
+  const int t_end = min(L, t_begin + cb);
+  const int ntiles = (t_end - t_begin + RC::kT - 1) / RC::kT;
+
+  unsigned long long* sh_anc = reinterpret_cast<unsigned long long*>(smem + 2 * RC::kStage);
+  int* sh_par = reinterpret_cast<int*>(smem + 2 * RC::kStage + 512);
+  int* sh_pages = reinterpret_cast<int*>(smem + 2 * RC::kStage + 768);      // [kMaxChunkPages]
+
+  const bool touches_drafts = t_end > ctx;
+  if (touches_drafts) {
+    if (P.parent) {
+      if (tid < kMaxQ) sh_par[tid] = (tid < n) ? P.parent[q0 + tid] : -1;
+      __syncthreads();
+    }
+    if (tid < kMaxQ) {
+      unsigned long long mask = 0;
+      if (tid < n) {
+        if (P.parent) {
+          int a = tid;
+          for (int g = 0; g <= tid && a >= 0; ++g) {
+            mask |= 1ull << a;
+            const int p = sh_par[a];
+            a = (p >= a || p < -1) ? -1 : p;
+          }
+        } else {
+          mask = (2ull << tid) - 1ull;
+        }
+      }
+      sh_anc[tid] = mask;
+    }
+    __syncthreads();
+  }
+
+  // ---- this wave's block of 32 query rows ----
+  const int wrow0 = row0 + 32 * wave;
+  const bool active = wrow0 < R;                // wave-uniform
+  const int row = wrow0 + ln;
+  const bool valid = row < R;
+  const int node = valid ? row / P.G : 0;
+  const int gq = valid ? row % P.G : 0;
+  const unsigned long long my_anc = (touches_drafts && valid) ? sh_anc[node] : 0ull;
+  const int64_t grow = static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + gq;
+  bf16x8 qf[C::kQKSteps];
+  {
+    const uint16_t* qp = P.q + grow * D + 8 * lh;
+#pragma unroll
+    for (int ks = 0; ks < C::kQKSteps; ++ks) {
+      u32x4 v = zero4();
+      if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+      qf[ks] = as_bf16x8(v);
+    }
+  }
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 oacc[C::kDBlocks];
+#pragma unroll
+  for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+
+  // ---- cooperative tile loads ----
+  const int32_t* bt = P.block_table + static_cast<int64_t>(b) * P.max_pages;
+  const int64_t page_elems = static_cast<int64_t>(P.Hkv) * kPage * D;
+  const int64_t head_off = static_cast<int64_t>(kvh) * kPage * D;
+  const int vc = tid % RC::kCh;                 // V: 16-byte chunk of the token row
+  const int vg = tid / RC::kCh;                 // V: group of kTpt consecutive tokens
+  const int vtok0 = vg * RC::kTpt;              // first of them within the tile
+  u32x4 kr[RC::kLoads], vr[RC::kLoads];
+
+  // Page ids of the whole chunk go to LDS once, so that the tile loads depend on no global read.
+  const int lp0 = t_begin / kPage;
+  const int np = (t_end + kPage - 1) / kPage - lp0;          // >= 1 pages touched by this chunk
+  for (int i = tid; i < np; i += RC::kThreads) sh_pages[i] = bt[lp0 + i];
+  __syncthreads();
+
+  // Loads are unconditional (addresses clamped to the chunk's last page): positions past the
+  // end are masked out of the scores, and their V values are zeroed when staged.
+  // Every load instruction of a wave touches one cache page, so the page id is wave-uniform
+  // (scalar base) and only a small per-lane offset lives in a vector register.
+  constexpr int kTokPerLoadWg = RC::kThreads / RC::kCh;               // tokens one load j of the workgroup covers
+  const int k_tok_in_load = tid / RC::kCh;                            // token of this lane within load j
+  const int k_lane_off = (k_tok_in_load % kPage) * D + (tid % RC::kCh) * 8;
+  const int k_page_in_load = k_tok_in_load / kPage;                   // wave-uniform
+  const int v_lane_off = (vtok0 % kPage) * D + vc * 8;
+  auto issue_loads = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < RC::kLoads; ++j) {
+      const int pidx = (RC::kT * t + j * kTokPerLoadWg) / kPage + k_page_in_load;
+      const int page = __builtin_amdgcn_readfirstlane(sh_pages[min(pidx, np - 1)]);
+      const uint16_t* base = P.k_pool + page * page_elems + head_off;
+      kr[j] = *reinterpret_cast<const u32x4*>(base + k_lane_off);
+    }
+    const int page = __builtin_amdgcn_readfirstlane(sh_pages[min((RC::kT * t + vtok0) / kPage, np - 1)]);
+    const uint16_t* vp = P.v_pool + page * page_elems + head_off + v_lane_off;
+#pragma unroll
+    for (int i = 0; i < RC::kTpt; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vp + i * D);
+  };
+
+  auto store_tile = [&](int stage, int t) {
+    unsigned char* k_lds = smem + stage * RC::kStage;
+    unsigned char* v_lds = k_lds + RC::kKBytes;
+#pragma unroll
+    for (int j = 0; j < RC::kLoads; ++j) {
+      const int tk = j * (RC::kThreads / RC::kCh) + tid / RC::kCh;
+      *reinterpret_cast<u32x4*>(k_lds + tk * RC::kKStride + (tid % RC::kCh) * 16) = kr[j];
+    }
+    // transposed V: token order inside each 16-token group follows the MFMA operand layout
+    const int s16 = vtok0 / 16, u = vtok0 % 16;
+    const int a4 = u >> 2, sub = u & 3;
+    const int pos = 8 * (a4 & 1) + 4 * (a4 >> 1) + sub;
+    const int col = (16 * s16 + pos) * 2;
+    // never multiply stale cache slots (past ctx+n) into O: stage them as zeros
+    const int left = L - (t_begin + RC::kT * t + vtok0);      // tokens of this thread that exist
+#pragma unroll
+    for (int i = 0; i < RC::kTpt; ++i)
+      if (i >= left) vr[i] = zero4();
+    const u32x4 w0 = vr[0], w1 = vr[1];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const uint32_t sel = half ? 0x07060302u : 0x05040100u;
+        const int vrow = (2 * k + half) * 18 + vc;
+        unsigned char* dst = v_lds + vrow * RC::kVStride + col;
+        if constexpr (RC::kTpt == 4) {
+          const uint32_t w2k = vr[2][k], w3k = vr[3][k];
+          uint2 o;
+          o.x = __builtin_amdgcn_perm(w1[k], w0[k], sel);
+          o.y = __builtin_amdgcn_perm(w3k, w2k, sel);
+          *reinterpret_cast<uint2*>(dst) = o;
+        } else {
+          *reinterpret_cast<uint32_t*>(dst) = __builtin_amdgcn_perm(w1[k], w0[k], sel);
+        }
+      }
+    }
+  };
+
+  auto compute_tile = [&](int stage, int t) {
+    const unsigned char* k_lds = smem + stage * RC::kStage;
+    const unsigned char* v_lds = k_lds + RC::kKBytes;
+#pragma unroll 1
+    for (int tb = 0; tb < RC::kT / 32; ++tb) {
+      const int tok0 = t_begin + RC::kT * t + 32 * tb;
+      if (tok0 >= t_end) break;
+      f32x16 sacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < C::kQKSteps; ++ks) {
+        const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(k_lds + (32 * tb + ln) * RC::kKStride + 32 * ks + 16 * lh));
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
+      }
+      const bool need_mask = tok0 + 32 > ctx;
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = sacc[r];
+        if (need_mask) {
+          const int pos = tok0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          const bool ok = pos < ctx || (pos < L && ((my_anc >> ((pos - ctx) & 63)) & 1ull));
+          v = ok ? v : -INFINITY;
+          sacc[r] = v;
+        }
+        tmax = fmaxf(tmax, v);
+      }
+      tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+      const float m_new = fmaxf(m_run, tmax);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run - m_safe);
+      if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      }
+      // P^T in two bf16 terms (hi + rounding residual), 16 tokens at a time, fed straight to PV
+      float psum = 0.f;
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        u32x4 hi, lo;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float p0 = fast_exp2(fmaf(sacc[8 * s + 2 * j], P.c, -m_safe));
+          const float p1 = fast_exp2(fmaf(sacc[8 * s + 2 * j + 1], P.c, -m_safe));
+          psum += p0 + p1;
+          const uint32_t h = pack_bf16(p0, p1);
+          hi[j] = h;
+          lo[j] = pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
+        }
+        const bf16x8 phi = __builtin_bit_cast(bf16x8, hi), plo = __builtin_bit_cast(bf16x8, lo);
+#pragma unroll
+        for (int db = 0; db < C::kDBlocks; ++db) {
+          const int d = 32 * db + ln;
+          const int vrow = (d & 7) * 18 + (d >> 3);
+          const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(v_lds + vrow * RC::kVStride + 64 * tb + 32 * s + 16 * lh));
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, phi, oacc[db], 0, 0, 0);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plo, oacc[db], 0, 0, 0);
+        }
+      }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+    }
+  };
+
+  // ---- pipeline: tile t is computed from LDS while tile t+1 sits in registers ----
+  issue_loads(0);
+  store_tile(0, 0);
+  if (ntiles > 1) issue_loads(1);
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    if (active) compute_tile(t & 1, t);
+    if (t + 1 < ntiles) {
+      store_tile((t + 1) & 1, t + 1);
+      if (t + 2 < ntiles) issue_loads(t + 2);
+    }
+    __syncthreads();
+  }
+
+  // ---- write this wave's rows ----
+  if (!active) return;
+  l_run += __shfl_xor(l_run, 32, kWave);
+  if (!valid) return;
+  if (nchunks == 1) {
+    const float inv = 1.f / l_run;
+#pragma unroll
+    for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int d = 32 * db + 8 * r4 + 4 * lh;
+        const float x0 = oacc[db][4 * r4] * inv, x1 = oacc[db][4 * r4 + 1] * inv;
+        const float x2 = oacc[db][4 * r4 + 2] * inv, x3 = oacc[db][4 * r4 + 3] * inv;
+        if (P.out_f32) {
+          *reinterpret_cast<float4*>(static_cast<float*>(P.out) + grow * D + d) = make_float4(x0, x1, x2, x3);
+        } else {
+          uint2 o;
+          o.x = pack_bf16(x0, x1);
+          o.y = pack_bf16(x2, x3);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(P.out) + grow * D + d) = o;
+        }
+      }
+    if (P.lse && lh == 0) P.lse[grow] = (m_run + log2f(l_run)) * static_cast<float>(kLn2);
+  } else {
+    float* o = P.ws_o + (grow * P.max_chunks + chunk) * D;
+#pragma unroll
+    for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int d = 32 * db + 8 * r4 + 4 * lh;
+        *reinterpret_cast<float4*>(o + d) =
+            make_float4(oacc[db][4 * r4], oacc[db][4 * r4 + 1], oacc[db][4 * r4 + 2], oacc[db][4 * r4 + 3]);
+      }
+    if (lh == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(m_run, l_run);
+  }
+}
+
 // Merge the per-chunk partials of every (query row, head) that spans several chunks.
 template <int D>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P, int total_rows) {
@@ -488,7 +791,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P, int tot
 // host side
 // ----------------------------------------------------------------------------------
 struct AttnPlan {
-  int nqb;            // query blocks per workgroup (template instance)
+  int kind;           // 0: token-split kernel (<= 32 rows per KV head), 1: row-split, 4 waves, 2: row-split, 8 waves
+  int rows_per_wg;
   int row_groups;
   int chunk_tokens;
   int max_chunks;
@@ -498,17 +802,26 @@ static AttnPlan make_plan(const AttnArgs& a) {
   AttnPlan p;
   const int G = a.Hq / a.Hkv;
   const int max_rows = a.max_q * G;
-  p.nqb = max_rows <= 32 ? 1 : (max_rows <= 64 ? 2 : 4);
-  p.row_groups = (max_rows + 32 * p.nqb - 1) / (32 * p.nqb);
+  if (max_rows <= 32) { p.kind = 0; p.rows_per_wg = 32; }
+  else if (max_rows <= 128 || a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
+  else { p.kind = 2; p.rows_per_wg = 256; }
+  p.row_groups = (max_rows + p.rows_per_wg - 1) / p.rows_per_wg;
+  const int gran = p.kind == 0 ? kTile : 64;              // chunks are whole tiles
   const int64_t max_tok = static_cast<int64_t>(a.max_pages) * a.page;
   int64_t tok = a.kv_hint > 0 ? a.kv_hint : static_cast<int64_t>(a.B) * max_tok;
-  // aim at ~4 workgroups per compute unit so that the dispatcher can balance ragged lengths
-  const int64_t jobs_target = 1024;
+  // Workgroups to aim for.  Each one pays a fixed prologue/epilogue, so uniform batches want
+  // about one per compute unit; ragged ones need more for the dispatcher to balance lengths.
+  int64_t jobs_target = p.kind == 0 ? 256 : 512;
+  if (const char* e = getenv("SPECV_ATTN_JOBS")) {      // development knob for sweeps
+    const long v = atol(e);
+    if (v > 0) jobs_target = v;
+  }
   int64_t chunk = (tok * a.Hkv * p.row_groups + jobs_target - 1) / jobs_target;
   if (chunk < 256) chunk = 256;
-  chunk = (chunk + kTile - 1) / kTile * kTile;
-  if (chunk > max_tok) chunk = (max_tok + kTile - 1) / kTile * kTile;
-  if (chunk < kTile) chunk = kTile;
+  chunk = (chunk + gran - 1) / gran * gran;
+  if (chunk > max_tok) chunk = (max_tok + gran - 1) / gran * gran;
+  if (p.kind != 0 && chunk > 16384) chunk = 16384;          // the row-split kernel keeps a chunk's page ids in LDS
+  if (chunk < gran) chunk = gran;
   p.chunk_tokens = static_cast<int>(chunk);
   p.max_chunks = static_cast<int>((max_tok + chunk - 1) / chunk);
   if (p.max_chunks < 1) p.max_chunks = 1;
@@ -522,22 +835,37 @@ size_t attn_workspace_bytes(const AttnArgs& a) {
   return rows * p.max_chunks * (a.D + 2) * sizeof(float) + 256;
 }
 
-template <int D, int NQB>
+template <typename K>
+static int set_lds_once(K kernel, size_t lds, bool& done) {
+  if (!done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(lds)) != hipSuccess)
+      return -6;
+    done = true;
+  }
+  return 0;
+}
+
+template <int D>
 static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
   using C = AttnCfg<D>;
-  constexpr size_t kMerge = kAttnWaves * 32 * C::kORedStride * sizeof(float) + (2 * kAttnWaves + 2) * NQB * 32 * sizeof(float);
+  constexpr size_t kMerge = kAttnWaves * 32 * C::kORedStride * sizeof(float) + (2 * kAttnWaves + 2) * 32 * sizeof(float);
   constexpr size_t kTiles = static_cast<size_t>(kAttnWaves) * C::kWaveLds;
   static_assert(kMerge <= kTiles, "merge buffers must fit in the tile memory");
-  const size_t lds = kTiles;
   static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_stream_kernel<D, NQB>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
-      return -6;
-    attr_done = true;
-  }
+  if (set_lds_once(&attn_stream_kernel<D, 1>, kTiles, attr_done) != 0) return -6;
   dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
-  hipLaunchKernelGGL((attn_stream_kernel<D, NQB>), grid, dim3(kAttnThreads), lds, stream, P);
+  hipLaunchKernelGGL((attn_stream_kernel<D, 1>), grid, dim3(kAttnThreads), kTiles, stream, P);
+  return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+template <int D, int NW>
+static int launch_rows(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
+  using RC = RowsCfg<D, NW>;
+  static bool attr_done = false;
+  if (set_lds_once(&attn_rows_kernel<D, NW>, RC::kLds, attr_done) != 0) return -6;
+  dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
+  hipLaunchKernelGGL((attn_rows_kernel<D, NW>), grid, dim3(RC::kThreads), RC::kLds, stream, P);
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
@@ -559,15 +887,9 @@ int launch_attn(const AttnArgs& a, hipStream_t stream) {
   P.c = a.scale * kLog2e;
   P.out_f32 = (a.out_dtype == kF32);
   int rc;
-  if (a.D == 128) {
-    if (plan.nqb == 1) rc = launch_stream<128, 1>(P, plan, a.B, a.Hkv, stream);
-    else if (plan.nqb == 2) rc = launch_stream<128, 2>(P, plan, a.B, a.Hkv, stream);
-    else rc = launch_stream<128, 4>(P, plan, a.B, a.Hkv, stream);
-  } else {
-    if (plan.nqb == 1) rc = launch_stream<64, 1>(P, plan, a.B, a.Hkv, stream);
-    else if (plan.nqb == 2) rc = launch_stream<64, 2>(P, plan, a.B, a.Hkv, stream);
-    else rc = launch_stream<64, 4>(P, plan, a.B, a.Hkv, stream);
-  }
+  if (plan.kind == 0) rc = a.D == 128 ? launch_stream<128>(P, plan, a.B, a.Hkv, stream) : launch_stream<64>(P, plan, a.B, a.Hkv, stream);
+  else if (plan.kind == 1) rc = a.D == 128 ? launch_rows<128, 4>(P, plan, a.B, a.Hkv, stream) : launch_rows<64, 4>(P, plan, a.B, a.Hkv, stream);
+  else rc = launch_rows<128, 8>(P, plan, a.B, a.Hkv, stream);
   if (rc != 0) return rc;
   if (plan.max_chunks > 1) {
     const int total_rows = static_cast<int>(rows);
