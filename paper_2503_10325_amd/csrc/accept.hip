@@ -100,6 +100,7 @@ void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void*
 constexpr int kWalkThreads = 1024;
 constexpr int kWalkWaves = kWalkThreads / kWave;
 constexpr int kMaxNodes = 64;
+constexpr int kMaxBlocksPerSeg = 256;      // vocabularies up to 16 * 256 * 512 = 2M tokens
 
 struct RowStat {
   float m;    // largest logit of the row
@@ -128,34 +129,47 @@ struct WalkRows {
 };
 
 // Weight of token class v at residual level L (L rejections so far at this node):
-//   level 0: p_v;  level k>=1: max(0, w_{k-1}(v)/R_{k-1} - q_v)  with R_{-1} := 1... written
-//   out: r_0 = p; w_k = max(0, r_{k-1} - q); r_k = w_k / R_k.
-__device__ __forceinline__ double level_weight(double p, double q, int L, const double* __restrict__ inv_R) {
-  double r = p;
+//   r_0 = p;  w_k = max(0, r_{k-1} - q);  r_k = w_k / R_k,  R_k = sum_v w_k(v).
+// The weight of level L is w_L (unnormalised; p itself at level 0).  Per-class values are
+// fp32 (their relative error, ~1e-7, is that of the hardware exp2 anyway); every sum over
+// classes is carried in fp64.
+__device__ __forceinline__ float level_weight(float p, float q, int L, const float* __restrict__ inv_R) {
+  float r = p;
   for (int k = 0; k < L; ++k) {
-    double w = r - q;
-    w = w > 0.0 ? w : 0.0;
+    const float w = fmaxf(r - q, 0.f);
     r = (k + 1 < L) ? w * inv_R[k] : w;      // the last level stays unnormalised
   }
   return r;
 }
 
+// Weights of eight consecutive token classes from their logits (q: logits or probabilities).
+__device__ __forceinline__ void weights_from(const WalkRows& R, const float (&lp)[8], const float (&lq)[8],
+                                             int n_valid, float c, int L, const float* __restrict__ inv_R,
+                                             float (&w)[8]) {
+  const float t_invz = static_cast<float>(R.t_invz), q_invz = static_cast<float>(R.q_invz);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float p = fast_exp2((lp[j] - R.t_m) * c) * t_invz;
+    float q = 0.f;
+    if (L > 0) q = R.q_is_probs ? lq[j] : fast_exp2((lq[j] - R.q_m) * c) * q_invz;
+    w[j] = (j < n_valid) ? level_weight(p, q, L, inv_R) : 0.f;
+  }
+}
+
 template <bool VEC>
 __device__ __forceinline__ void weights8(const WalkRows& R, int e0, int V, float c, int L,
-                                         const double* __restrict__ inv_R, double (&w)[8]) {
+                                         const float* __restrict__ inv_R, float (&w)[8]) {
   float lp[8], lq[8];
   load8<VEC>(R.t_base, R.t_dtype, R.t_off, e0, V, lp);
   if (L > 0) load8<VEC>(R.q_base, R.q_dtype, R.q_off, e0, V, lq);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const double p = static_cast<double>(fast_exp2((lp[j] - R.t_m) * c)) * R.t_invz;
-    double q = 0.0;
-    if (L > 0) {
-      if (R.q_is_probs) q = (e0 + j < V) ? static_cast<double>(lq[j]) : 0.0;
-      else q = static_cast<double>(fast_exp2((lq[j] - R.q_m) * c)) * R.q_invz;
-    }
-    w[j] = level_weight(p, q, L, inv_R);
-  }
+  weights_from(R, lp, lq, min(8, V - e0), c, L, inv_R, w);
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack_bf16x8(u32x4 r, float (&x)[8]) {
+  x[0] = bf16_lo(r[0]); x[1] = bf16_hi(r[0]); x[2] = bf16_lo(r[1]); x[3] = bf16_hi(r[1]);
+  x[4] = bf16_lo(r[2]); x[5] = bf16_hi(r[2]); x[6] = bf16_lo(r[3]); x[7] = bf16_hi(r[3]);
 }
 
 struct AcceptParams {
@@ -176,7 +190,9 @@ struct AcceptParams {
   const SegStat* stats;
 };
 
-template <bool VEC>
+// FAST: 16-byte aligned rows with both logit matrices in bf16 (the default layout): the full
+// passes keep four 512-token blocks in flight per wave.
+template <bool VEC, bool FAST>
 __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams P) {
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -190,7 +206,9 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   const int seg_w = (((V + kWalkWaves - 1) / kWalkWaves) + 511) / 512 * 512;
 
   __shared__ double sh_wave_sum[kWalkWaves];
-  __shared__ double sh_inv_R[kMaxNodes];
+  __shared__ double sh_blk[kWalkWaves * kMaxBlocksPerSeg];   // per 512-token block of every wave segment
+  __shared__ double sh_inv_R[kMaxNodes];     // 1 / R_k for the scalar accept tests
+  __shared__ float sh_inv_Rf[kMaxNodes];     // the same, fp32, for the per-class passes
   __shared__ int sh_token;
   // per-request tables filled once, in parallel, so that the walk itself touches no global memory
   __shared__ float sh_tm[kMaxNodes + 1];       // target local row i: max logit
@@ -202,41 +220,55 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   __shared__ float sh_u[kMaxNodes];
 
   const bool q_is_probs = (P.q_kind == 1);
-  if (wave == 0) {
-    if (lane <= n) {
-      const RowStat ps = merge_stats(P.stats, trow0 + lane, P.nseg, c);
-      sh_tm[lane] = ps.m;
-      sh_tinvz[lane] = 1.0 / ps.z;
-    }
-  } else if (wave == 1) {
+  const double u_res = static_cast<double>(P.u_resample[b]);      // needed last; fetched first
+  // (1) node arrays
+  if (tid < n) {
+    int par = P.parent ? P.parent[o + tid] : tid - 1;
+    if (par < -1 || par >= tid) par = -1;
+    sh_par[tid] = par;
+    sh_tok[tid] = P.draft_tokens[o + tid];
+    sh_qrow[tid] = P.q_row[o + tid];
+    sh_u[tid] = P.u_accept[o + tid];
+    if (P.dbg_ratio) P.dbg_ratio[o + tid] = __builtin_nanf("");
+  }
+  __syncthreads();
+  // (2) in one round trip: the two logits of every drafted token (last wave) and the merged
+  // statistics of the n+1 target rows and n draft rows (groups of 16 lanes, one segment each)
+  if (wave == kWalkWaves - 1) {
     if (lane < n) {
-      int par = P.parent ? P.parent[o + lane] : lane - 1;
-      if (par < -1 || par >= lane) par = -1;
-      const int qr = P.q_row[o + lane];
-      sh_par[lane] = par;
-      sh_tok[lane] = P.draft_tokens[o + lane];
-      sh_qrow[lane] = qr;
-      sh_u[lane] = P.u_accept[o + lane];
-      if (!q_is_probs) {
-        const RowStat qs = merge_stats(P.stats, static_cast<int64_t>(P.n_t_rows) + qr, P.nseg, c);
-        sh_qm[lane] = qs.m;
-        sh_qinvz[lane] = 1.0 / qs.z;
+      const int x = sh_tok[lane];
+      sh_px[lane] = static_cast<double>(load_logit(P.target, P.t_dtype, (trow0 + 1 + sh_par[lane]) * static_cast<int64_t>(V) + x));
+      sh_qx[lane] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, static_cast<int64_t>(sh_qrow[lane]) * V + x));
+    }
+  } else {
+    const int n_rows = (n + 1) + (q_is_probs ? 0 : n);
+    const int sl = tid & 15;
+    for (int ri = tid >> 4; ri < n_rows; ri += (kWalkThreads - kWave) / 16) {
+      const int64_t srow = (ri <= n) ? trow0 + ri : static_cast<int64_t>(P.n_t_rows) + sh_qrow[ri - n - 1];
+      float m = -INFINITY;
+      for (int sg = sl; sg < P.nseg; sg += 16) m = fmaxf(m, P.stats[srow * P.nseg + sg].m);
+#pragma unroll
+      for (int d = 8; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 16));
+      double z = 0.0;
+      for (int sg = sl; sg < P.nseg; sg += 16) {
+        const SegStat st = P.stats[srow * P.nseg + sg];
+        if (st.m != -INFINITY) z += st.z * exp2(static_cast<double>(st.m - m) * static_cast<double>(c));
       }
-      if (P.dbg_ratio) P.dbg_ratio[o + lane] = __builtin_nanf("");
+#pragma unroll
+      for (int d = 8; d > 0; d >>= 1) z += __shfl_xor(z, d, 16);
+      if (sl == 0) {
+        if (ri <= n) { sh_tm[ri] = m; sh_tinvz[ri] = 1.0 / z; }
+        else { sh_qm[ri - n - 1] = m; sh_qinvz[ri - n - 1] = 1.0 / z; }
+      }
     }
   }
   __syncthreads();
+  // (3) p(x), q(x) of every node
   if (tid < n) {
-    const int x = sh_tok[tid], par = sh_par[tid];
-    const int64_t prow = trow0 + 1 + par;
-    const double lp = static_cast<double>(load_logit(P.target, P.t_dtype, prow * V + x));
-    sh_px[tid] = exp2((lp - static_cast<double>(sh_tm[par + 1])) * static_cast<double>(c)) * sh_tinvz[par + 1];
-    const int64_t qoff = static_cast<int64_t>(sh_qrow[tid]) * V + x;
-    if (q_is_probs) sh_qx[tid] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, qoff));
-    else {
-      const double lq = static_cast<double>(load_logit(P.draft_q, P.q_dtype, qoff));
-      sh_qx[tid] = exp2((lq - static_cast<double>(sh_qm[tid])) * static_cast<double>(c)) * sh_qinvz[tid];
-    }
+    const int par = sh_par[tid];
+    sh_px[tid] = exp2((sh_px[tid] - static_cast<double>(sh_tm[par + 1])) * static_cast<double>(c)) * sh_tinvz[par + 1];
+    if (!q_is_probs)
+      sh_qx[tid] = exp2((sh_qx[tid] - static_cast<double>(sh_qm[tid])) * static_cast<double>(c)) * sh_qinvz[tid];
   }
   __syncthreads();
 
@@ -246,21 +278,62 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   WalkRows R;
   R.t_base = P.target; R.t_dtype = P.t_dtype;
   R.q_base = P.draft_q; R.q_dtype = P.q_dtype; R.q_is_probs = q_is_probs;
+  R.t_off = 0; R.t_m = 0.f; R.t_invz = 0.0;
   R.q_off = 0; R.q_m = 0.f; R.q_invz = 0.0; R.have_q = 0;
 
-  // one full pass at residual level L: per-wave sums to LDS, returns the total
+  const int e_begin = wave * seg_w;
+  const int e_end = min(V, e_begin + seg_w);
+  const int nit = e_end > e_begin ? (e_end - e_begin + 511) / 512 : 0;
+
+  // One full pass at residual level L: block sums and per-wave sums to LDS, returns the total.
   auto full_pass = [&](int L) -> double {
     double acc = 0.0;
-    const int e_begin = wave * seg_w;
-    const int e_end = min(V, e_begin + seg_w);
-    for (int e0 = e_begin + lane * 8; e0 < e_end; e0 += 512) {
-      double w[8];
-      weights8<VEC>(R, e0, V, c, L, sh_inv_R, w);
+    __syncthreads();                 // previous readers of the sums are done
+    if constexpr (FAST) {
+      const uint16_t* tp = static_cast<const uint16_t*>(R.t_base) + R.t_off;
+      const uint16_t* qp = static_cast<const uint16_t*>(R.q_base) + R.q_off;
+      for (int it0 = 0; it0 < nit; it0 += 4) {
+        u32x4 rp[4], rq[4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc += w[j];
+        for (int u = 0; u < 4; ++u) {
+          const int e0 = min(e_begin + (it0 + u) * 512 + lane * 8, V - 8);     // clamped; masked below
+          rp[u] = *reinterpret_cast<const u32x4*>(tp + e0);
+          if (L > 0) rq[u] = *reinterpret_cast<const u32x4*>(qp + e0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int it = it0 + u;
+          if (it < nit) {
+            const int e0 = e_begin + it * 512 + lane * 8;
+            float lp[8], lq[8];
+            unpack_bf16x8(rp[u], lp);
+            if (L > 0) unpack_bf16x8(rq[u], lq);
+            float w[8];
+            weights_from(R, lp, lq, e0 < e_end ? 8 : 0, c, L, sh_inv_Rf, w);
+            float lsf = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) lsf += w[j];
+            const double ls = wave_sum(static_cast<double>(lsf));
+            if (lane == 0) sh_blk[wave * kMaxBlocksPerSeg + it] = ls;
+            acc += ls;
+          }
+        }
+      }
+    } else {
+      for (int it = 0; it < nit; ++it) {
+        const int e0 = e_begin + it * 512 + lane * 8;
+        float lsf = 0.f;
+        if (e0 < e_end) {
+          float w[8];
+          weights8<VEC>(R, e0, V, c, L, sh_inv_Rf, w);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) lsf += w[j];
+        }
+        const double ls = wave_sum(static_cast<double>(lsf));
+        if (lane == 0) sh_blk[wave * kMaxBlocksPerSeg + it] = ls;
+        acc += ls;
+      }
     }
-    acc = wave_sum(acc);
-    __syncthreads();                 // previous readers of sh_wave_sum are done
     if (lane == 0) sh_wave_sum[wave] = acc;
     __syncthreads();
     double tot = 0.0;
@@ -269,7 +342,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   };
 
   int level = 0;          // rejections so far at the current node
-  int sums_level = -1;    // level whose per-wave sums sit in sh_wave_sum (-1: none)
+  int sums_level = -1;    // level whose sums sit in LDS (-1: none)
   double total = 0.0;     // total of those sums
 
   for (int guard = 0; guard <= kMaxNodes; ++guard) {
@@ -309,7 +382,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       const double mass = full_pass(level + 1);
       if (mass > 0.0) {
         __syncthreads();
-        if (tid == 0) sh_inv_R[level] = 1.0 / mass;
+        if (tid == 0) { sh_inv_R[level] = 1.0 / mass; sh_inv_Rf[level] = static_cast<float>(1.0 / mass); }
         __syncthreads();
         ++level;
         sums_level = level;
@@ -326,13 +399,13 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     }
     // no child, or every child rejected: draw from the level's weights by inverse CDF
     if (sums_level != level) { total = full_pass(level); sums_level = level; }
-    const double target = static_cast<double>(P.u_resample[b]) * total;
+    const double target = u_res * total;
     int ws = -1;
     double before = 0.0;
     for (int w = 0; w < kWalkWaves; ++w) {
-      const double s = sh_wave_sum[w];
-      if (before + s > target) { ws = w; break; }
-      before += s;
+      const double sw = sh_wave_sum[w];
+      if (before + sw > target) { ws = w; break; }
+      before += sw;
     }
     if (ws < 0) {                    // rounding left no crossing: last wave with positive mass
       for (int w = kWalkWaves - 1; w >= 0; --w) if (sh_wave_sum[w] > 0.0) { ws = w; break; }
@@ -340,60 +413,67 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       before = 0.0;
       for (int w = 0; w < ws; ++w) before += sh_wave_sum[w];
     }
-    if (tid == 0) sh_token = -1;
-    __syncthreads();
-    if (wave == ws) {
-      const int e_begin = ws * seg_w;
-      const int e_end = min(V, e_begin + seg_w);
-      double run = before;
-      int found = -1, last_pos = -1;
-      for (int e_it = e_begin; e_it < e_end && found < 0; e_it += 512) {
-        const int e0 = e_it + lane * 8;
-        double w[8];
-        if (e0 < e_end) weights8<VEC>(R, e0, V, c, level, sh_inv_R, w);
-        else {
+    // block of 512 tokens inside segment ws (its sums were kept by the pass)
+    const int ws_begin = ws * seg_w;
+    const int ws_end = min(V, ws_begin + seg_w);
+    const int ws_nit = ws_end > ws_begin ? (ws_end - ws_begin + 511) / 512 : 0;
+    const double* blk = sh_blk + ws * kMaxBlocksPerSeg;
+    int it_hit = -1;
+    double run = before;
+    for (int it = 0; it < ws_nit; ++it) {
+      const double sblk = blk[it];
+      if (run + sblk > target) { it_hit = it; break; }
+      run += sblk;
+    }
+    if (it_hit < 0) {                // rounding: last block of the segment with positive mass
+      for (int it = ws_nit - 1; it >= 0; --it) if (blk[it] > 0.0) { it_hit = it; break; }
+      if (it_hit < 0) it_hit = 0;
+      run = before;
+      for (int it = 0; it < it_hit; ++it) run += blk[it];
+    }
+    if (wave == 0) {
+      const int e0 = ws_begin + it_hit * 512 + lane * 8;
+      float w[8];
+      if (e0 < ws_end) weights8<VEC>(R, e0, V, c, level, sh_inv_Rf, w);
+      else {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) w[j] = 0.0;
-        }
-        double ls = 0.0;
-        int my_last = -1;
+        for (int j = 0; j < 8; ++j) w[j] = 0.f;
+      }
+      float lsf = 0.f;                 // summed exactly as the pass did, so the block sums agree
+      int my_last = -1;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { ls += w[j]; if (w[j] > 0.0) my_last = e0 + j; }
-        // inclusive scan of lane sums
-        double inc = ls;
+      for (int j = 0; j < 8; ++j) { lsf += w[j]; if (w[j] > 0.f) my_last = e0 + j; }
+      const double ls = static_cast<double>(lsf);
+      double inc = ls;                 // inclusive scan of the lane sums
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-          const double t = __shfl_up(inc, d, kWave);
-          if (lane >= d) inc += t;
-        }
-        const double it_total = __shfl(inc, 63, kWave);
-        const unsigned long long cross = __ballot(run + inc > target);
-        if (cross) {
-          const int fl = __ffsll(static_cast<long long>(cross)) - 1;
-          int tok = -1;
-          if (lane == fl) {
-            double acc = run + inc - ls;
+      for (int d = 1; d < 64; d <<= 1) {
+        const double tq = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += tq;
+      }
+      const unsigned long long cross = __ballot(run + inc > target);
+      int found = -1;
+      if (cross) {
+        const int fl = __ffsll(static_cast<long long>(cross)) - 1;
+        int tok = -1;
+        if (lane == fl) {
+          double acc = run + inc - ls;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              acc += w[j];
-              if (tok < 0 && acc > target && w[j] > 0.0) tok = e0 + j;
-            }
-            if (tok < 0) tok = my_last;      // rounding inside the lane: its last positive class
+          for (int j = 0; j < 8; ++j) {
+            acc += static_cast<double>(w[j]);
+            if (tok < 0 && acc > target && w[j] > 0.f) tok = e0 + j;
           }
-          found = __shfl(tok, fl, kWave);
+          if (tok < 0) tok = my_last;      // rounding inside the lane: its last positive class
         }
-        // remember the last class with positive weight seen so far
+        found = __shfl(tok, fl, kWave);
+      }
+      if (found < 0) {                     // rounding across lanes: last positive class of the block
         int ml = my_last;
 #pragma unroll
         for (int d = 32; d > 0; d >>= 1) ml = max(ml, __shfl_xor(ml, d, kWave));
-        last_pos = max(last_pos, ml);
-        run += it_total;
+        found = ml >= 0 ? ml : min(V - 1, ws_begin + it_hit * 512);
       }
-      if (found < 0) found = last_pos >= 0 ? last_pos : min(V - 1, e_begin);
-      if (lane == 0) sh_token = found;
+      if (lane == 0 && depth < P.out_stride) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + depth] = found;
     }
-    __syncthreads();
-    if (tid == 0 && depth < P.out_stride) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + depth] = sh_token;
     break;
   }
   if (tid == 0) {
@@ -424,8 +504,10 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   P.accept_len = a.accept_len; P.out_tokens = a.out_tokens; P.out_stride = a.out_stride;
   P.stop_node = a.stop_node; P.dbg_ratio = a.dbg_ratio; P.stats = stats;
   const bool vec = (a.V % 8 == 0);
-  if (vec) hipLaunchKernelGGL(accept_walk_kernel<true>, dim3(a.B), dim3(kWalkThreads), 0, stream, P);
-  else hipLaunchKernelGGL(accept_walk_kernel<false>, dim3(a.B), dim3(kWalkThreads), 0, stream, P);
+  const bool fast = vec && a.V >= 8 && a.t_dtype == kBF16 && a.q_dtype == kBF16 && a.q_kind == 0;
+  if (fast) hipLaunchKernelGGL((accept_walk_kernel<true, true>), dim3(a.B), dim3(kWalkThreads), 0, stream, P);
+  else if (vec) hipLaunchKernelGGL((accept_walk_kernel<true, false>), dim3(a.B), dim3(kWalkThreads), 0, stream, P);
+  else hipLaunchKernelGGL((accept_walk_kernel<false, false>), dim3(a.B), dim3(kWalkThreads), 0, stream, P);
 }
 
 }  // namespace specv

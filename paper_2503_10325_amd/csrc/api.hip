@@ -115,6 +115,7 @@ int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
   if (B < 0 || V <= 0 || total_nodes < 0 || n_q_rows < 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
   if (!(temperature > 0.f)) return SPEC_ERR_SHAPE;
   if (max_nodes_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (V > 2097152) return SPEC_ERR_UNSUPPORTED;        // the walk kernel indexes a row by 16 x 256 blocks of 512
   if (out_stride < max_nodes_per_req + 1) return SPEC_ERR_SHAPE;
   if ((target_dtype != SPEC_BF16 && target_dtype != SPEC_F32) || (q_dtype != SPEC_BF16 && q_dtype != SPEC_F32))
     return SPEC_ERR_UNSUPPORTED;
