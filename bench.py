@@ -78,8 +78,10 @@ class Step:
             self.fuse = runner.DeviceFuse(f, cfg.vocab, temperature=cfg.temperature,
                                           draft_logits_dev=torch.empty(0, device="cuda"))
             self.fuse.draft_logits = None
-            uniform = int(st.n.min()) == int(st.n.max())
-            # with a uniform draft length the fused [B, k] outputs are the flat node arrays
+            # Only for linear drafts of uniform length are the fused [B, k] outputs the flat node
+            # arrays (node j's draft row is row j).  Tree nodes index their parent's draft row, so
+            # tree and ragged workloads keep the generator's q_row / tokens.
+            uniform = st.parent is None and int(st.n.min()) == int(st.n.max())
             self.accept = runner.DeviceAccept(st, ai.target_logits, ai.draft_q,
                                               self.fuse.q_row.view(-1) if uniform else ai.q_row,
                                               self.fuse.fused_token.view(-1) if uniform else ai.draft_tokens,

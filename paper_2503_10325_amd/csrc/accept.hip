@@ -173,7 +173,7 @@ __device__ __forceinline__ void unpack_bf16x8(u32x4 r, float (&x)[8]) {
 }
 
 struct AcceptParams {
-  int B, V, n_t_rows, nseg;
+  int B, V, n_t_rows, n_q_rows, nseg;
   const int32_t* node_offsets;
   const int32_t* parent;
   const int32_t* draft_tokens;
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   const int seg_w = (((V + kWalkWaves - 1) / kWalkWaves) + 511) / 512 * 512;
 
   __shared__ double sh_wave_sum[kWalkWaves];
-  __shared__ double sh_blk[kWalkWaves * kMaxBlocksPerSeg];   // per 512-token block of every wave segment
+  __shared__ double sh_blk[kMaxBlocksPerSeg];   // sums of the 512-token blocks of the segment the draw falls in
   __shared__ double sh_inv_R[kMaxNodes];     // 1 / R_k for the scalar accept tests
   __shared__ float sh_inv_Rf[kMaxNodes];     // the same, fp32, for the per-class passes
   __shared__ int sh_token;
@@ -226,8 +226,10 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     int par = P.parent ? P.parent[o + tid] : tid - 1;
     if (par < -1 || par >= tid) par = -1;
     sh_par[tid] = par;
-    sh_tok[tid] = P.draft_tokens[o + tid];
-    sh_qrow[tid] = P.q_row[o + tid];
+    // indices come from device memory the host cannot check: clamp them so that a bad entry
+    // gives a wrong answer for that request instead of an out-of-bounds read
+    sh_tok[tid] = min(max(P.draft_tokens[o + tid], 0), V - 1);
+    sh_qrow[tid] = min(max(P.q_row[o + tid], 0), P.n_q_rows - 1);
     sh_u[tid] = P.u_accept[o + tid];
     if (P.dbg_ratio) P.dbg_ratio[o + tid] = __builtin_nanf("");
   }
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   const int e_end = min(V, e_begin + seg_w);
   const int nit = e_end > e_begin ? (e_end - e_begin + 511) / 512 : 0;
 
-  // One full pass at residual level L: block sums and per-wave sums to LDS, returns the total.
+  // One full pass at residual level L: per-wave sums to LDS, returns the total.
   auto full_pass = [&](int L) -> double {
     double acc = 0.0;
     __syncthreads();                 // previous readers of the sums are done
@@ -313,9 +315,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
             float lsf = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) lsf += w[j];
-            const double ls = wave_sum(static_cast<double>(lsf));
-            if (lane == 0) sh_blk[wave * kMaxBlocksPerSeg + it] = ls;
-            acc += ls;
+            acc += static_cast<double>(lsf);
           }
         }
       }
@@ -329,11 +329,10 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
 #pragma unroll
           for (int j = 0; j < 8; ++j) lsf += w[j];
         }
-        const double ls = wave_sum(static_cast<double>(lsf));
-        if (lane == 0) sh_blk[wave * kMaxBlocksPerSeg + it] = ls;
-        acc += ls;
+        acc += static_cast<double>(lsf);
       }
     }
+    acc = wave_sum(acc);
     if (lane == 0) sh_wave_sum[wave] = acc;
     __syncthreads();
     double tot = 0.0;
@@ -413,11 +412,25 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       before = 0.0;
       for (int w = 0; w < ws; ++w) before += sh_wave_sum[w];
     }
-    // block of 512 tokens inside segment ws (its sums were kept by the pass)
+    // block of 512 tokens inside segment ws: the 16 waves sum its blocks in parallel
     const int ws_begin = ws * seg_w;
     const int ws_end = min(V, ws_begin + seg_w);
     const int ws_nit = ws_end > ws_begin ? (ws_end - ws_begin + 511) / 512 : 0;
-    const double* blk = sh_blk + ws * kMaxBlocksPerSeg;
+    __syncthreads();
+    for (int it = wave; it < ws_nit; it += kWalkWaves) {
+      const int e0 = ws_begin + it * 512 + lane * 8;
+      float lsf = 0.f;
+      if (e0 < ws_end) {
+        float w[8];
+        weights8<VEC>(R, e0, V, c, level, sh_inv_Rf, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lsf += w[j];
+      }
+      const double ls = wave_sum(static_cast<double>(lsf));
+      if (lane == 0) sh_blk[it] = ls;
+    }
+    __syncthreads();
+    const double* blk = sh_blk;
     int it_hit = -1;
     double run = before;
     for (int it = 0; it < ws_nit; ++it) {
@@ -496,7 +509,7 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   SegStat* stats = static_cast<SegStat*>(a.workspace);
   launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream);
   AcceptParams P;
-  P.B = a.B; P.V = a.V; P.n_t_rows = n_t_rows; P.nseg = stats_segments(a.V);
+  P.B = a.B; P.V = a.V; P.n_t_rows = n_t_rows; P.n_q_rows = a.n_q_rows > 0 ? a.n_q_rows : 1; P.nseg = stats_segments(a.V);
   P.node_offsets = a.node_offsets; P.parent = a.parent; P.draft_tokens = a.draft_tokens;
   P.target = a.target; P.t_dtype = a.t_dtype;
   P.draft_q = a.draft_q; P.q_dtype = a.q_dtype; P.q_kind = a.q_kind;

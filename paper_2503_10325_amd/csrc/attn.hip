@@ -63,6 +63,16 @@ struct AttnParams {
   int out_f32;
 };
 
+#ifdef SPECV_PROFILE
+// Development-only cycle accounting of the token-split kernel (never part of a normal build).
+__device__ unsigned long long g_prof[8];
+#define PROF_T() clock64()
+#define PROF_ADD(i, v) do { if (lane == 0) atomicAdd(&g_prof[i], static_cast<unsigned long long>(v)); } while (0)
+#else
+#define PROF_T() 0ll
+#define PROF_ADD(i, v) do { } while (0)
+#endif
+
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -85,8 +95,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, x);
 }
 
-template <int D, int NQB>
-__global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_kernel(AttnParams P) {
+// Token-split kernel (up to 128 query rows per KV head and workgroup).  The 4 waves of a
+// workgroup take roles from the number of 32-row query blocks nqb of the request:
+//   nqb = 1: the four waves stream every 4th tile for the same query block;
+//   nqb = 2: two waves per query block, each streaming every 2nd tile;
+//   nqb = 3, 4: one wave per query block, streaming every tile.
+// Waves that share tokens fetch them separately (the repeats hit in L2: HBM traffic stays 1x).
+template <int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams P) {
   using C = AttnCfg<D>;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -101,9 +117,13 @@ __global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_
   const int ctx = P.ctx_len[b];
   const int L = ctx + n;
   const int R = n * P.G;
-  const int row0 = rg * (32 * NQB);
+  const int row0 = rg * 128;
   if (row0 >= R) return;
-  const int nqb = min(NQB, (R - row0 + 31) / 32);          // active query blocks of this workgroup
+  const int nqb = min(4, (R - row0 + 31) / 32);             // query blocks of this workgroup
+  const int nqbp = nqb <= 1 ? 1 : (nqb <= 2 ? 2 : 4);       // ... rounded up to a power of two
+  const int nslice = kAttnWaves / nqbp;                     // waves sharing one query block
+  const int my_qb = wave % nqbp, my_slice = wave / nqbp;
+  const bool wave_active = my_qb < nqb;                     // wave-uniform
   const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
   if (chunk >= nchunks) return;
   const int cb = (((L + nchunks - 1) / nchunks) + kTile - 1) & ~(kTile - 1);
@@ -118,10 +138,8 @@ __global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_
   // tile is staged, the merge statistics live behind the cross-wave reduction buffer.
   unsigned long long* sh_anc = reinterpret_cast<unsigned long long*>(smem);            // [64]
   int* sh_par = reinterpret_cast<int*>(smem + 512);                                    // [64]
-  float* sh_m = reinterpret_cast<float*>(smem + kAttnWaves * 32 * C::kORedStride * sizeof(float));  // [4][NQB*32]
-  float* sh_l = sh_m + kAttnWaves * NQB * 32;                                          // [4][NQB*32]
-  float* sh_M = sh_l + kAttnWaves * NQB * 32;                                          // [NQB*32]
-  float* sh_L = sh_M + NQB * 32;                                                       // [NQB*32]
+  float* sh_m = reinterpret_cast<float*>(smem + kAttnWaves * 32 * C::kORedStride * sizeof(float));  // [4][32]
+  float* sh_l = sh_m + kAttnWaves * 32;                                                // [4][32]
 
   // ---- ancestor-or-self masks of the draft nodes (only chunks that reach the drafts) ----
   const bool touches_drafts = t_end > ctx;
@@ -149,37 +167,30 @@ __global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_
     __syncthreads();
   }
 
-  // ---- this lane's query column in every query block ----
-  bf16x8 qf[NQB][C::kQKSteps];
-  unsigned long long my_anc[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int row = row0 + 32 * qb + ln;
-    const bool valid = row < R;
-    const int node = valid ? row / P.G : 0;
-    const int g = valid ? row % P.G : 0;
-    my_anc[qb] = (touches_drafts && valid) ? sh_anc[node] : 0ull;
-    const uint16_t* qp = P.q + (static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + g) * D + 8 * lh;
+  // ---- this lane's query column ----
+  const int row = row0 + 32 * my_qb + ln;
+  const bool valid = row < R;
+  const int node = valid ? row / P.G : 0;
+  const int gq = valid ? row % P.G : 0;
+  const unsigned long long my_anc = (touches_drafts && valid) ? sh_anc[node] : 0ull;
+  bf16x8 qf[C::kQKSteps];
+  {
+    const uint16_t* qp = P.q + (static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + gq) * D + 8 * lh;
 #pragma unroll
     for (int ks = 0; ks < C::kQKSteps; ++ks) {
       u32x4 v = zero4();
       if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
-      qf[qb][ks] = as_bf16x8(v);
+      qf[ks] = as_bf16x8(v);
     }
   }
   if (touches_drafts) __syncthreads();       // masks are in registers; the memory becomes tile space
 
-  float m_run[NQB], l_run[NQB];
-  f32x16 oacc[NQB][C::kDBlocks];
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 oacc[C::kDBlocks];
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
+  for (int db = 0; db < C::kDBlocks; ++db)
 #pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
-  }
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 
   // ---- lane roles for the loads ----
   const int kc = lane % C::kCh;              // 16-byte chunk within the token row
@@ -198,12 +209,19 @@ __global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_
 
   u32x4 kr[C::kLoads], vr[C::kLoads];
 
+  // Page ids are fetched one tile ahead of the K/V loads that need them, so the tile loads never
+  // wait on a dependent block-table read.
+  int pg[2] = {-1, -1};
+  auto fetch_pages = [&](int t) {
+    if (t < ntiles) {
+      const int tok0 = t_begin + kTile * t;
+      const int lp = tok0 / kPage;
+      pg[0] = bt[lp];
+      pg[1] = (tok0 + kPage < L) ? bt[lp + 1] : -1;
+    }
+  };
   auto issue_loads = [&](int t) {
     const int tok0 = t_begin + kTile * t;
-    const int lp = tok0 / kPage;
-    int pg[2];
-    pg[0] = bt[lp];
-    pg[1] = (tok0 + kPage < L) ? bt[lp + 1] : -1;
 #pragma unroll
     for (int j = 0; j < C::kLoads; ++j) {
       const int tk = j * C::kTokPerLoad + kt;
@@ -228,9 +246,16 @@ __global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_
     }
   };
 
-  int t = wave;
-  if (t < ntiles) issue_loads(t);
-  for (; t < ntiles; t += kAttnWaves) {
+  const long long prof_t0 = PROF_T();
+  long long prof_store = 0, prof_compute = 0, prof_tiles = 0;
+  int t = my_slice;
+  if (wave_active && t < ntiles) {
+    fetch_pages(t);
+    issue_loads(t);
+    fetch_pages(t + nslice);
+  }
+  for (; wave_active && t < ntiles; t += nslice) {
+    const long long prof_a = PROF_T();
     // ---- registers -> LDS ----
 #pragma unroll
     for (int j = 0; j < C::kLoads; ++j) {
@@ -255,185 +280,162 @@ __global__ __launch_bounds__(kAttnThreads, (NQB == 1 ? 2 : 1)) void attn_stream_
       }
     }
     const int tok0 = t_begin + kTile * t;
-    if (t + kAttnWaves < ntiles) issue_loads(t + kAttnWaves);
+    if (t + nslice < ntiles) {
+      issue_loads(t + nslice);
+      fetch_pages(t + 2 * nslice);
+    }
     wave_lds_fence();
+    const long long prof_b = PROF_T();
 
     // ---- S^T = K Q^T ----
-    f32x16 sacc[NQB];
+    f32x16 sacc;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::kQKSteps; ++ks) {
       const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(k_lds + ln * C::kKStride + 32 * ks + 16 * lh));
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb)
-        if (qb < nqb) sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[qb], 0, 0, 0);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
     }
 
-    // ---- mask, online softmax, P^T in bf16 ----
+    // ---- mask, online softmax ----
     const bool need_mask = tok0 + kTile > ctx;
-    bf16x8 pf[NQB][2], pl[NQB][2];       // P^T split into two bf16 terms (hi + lo)
+    float tmax = -INFINITY;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      if (qb < nqb) {
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = sacc[qb][r] * P.c;
-          if (need_mask) {
-            const int pos = tok0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            const bool ok = pos < ctx || (pos < L && ((my_anc[qb] >> ((pos - ctx) & 63)) & 1ull));
-            v = ok ? v : -INFINITY;
-          }
-          sacc[qb][r] = v;
-          tmax = fmaxf(tmax, v);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-        const float m_new = fmaxf(m_run[qb], tmax);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run[qb] - m_safe);
-        float psum = 0.f;
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = fast_exp2(sacc[qb][r] - m_safe);
-          psum += p[r];
-        }
-        // A single bf16 rounding of P (2^-9 relative) would dominate the output error; carrying
-        // the rounding residual in a second bf16 term keeps ~16 bits of every weight.
-        u32x4 f0, f1, g0, g1;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t h0 = pack_bf16(p[2 * j], p[2 * j + 1]);
-          const uint32_t h1 = pack_bf16(p[8 + 2 * j], p[8 + 2 * j + 1]);
-          f0[j] = h0;
-          f1[j] = h1;
-          g0[j] = pack_bf16(p[2 * j] - bf16_lo(h0), p[2 * j + 1] - bf16_hi(h0));
-          g1[j] = pack_bf16(p[8 + 2 * j] - bf16_lo(h1), p[8 + 2 * j + 1] - bf16_hi(h1));
-        }
-        pf[qb][0] = __builtin_bit_cast(bf16x8, f0);
-        pf[qb][1] = __builtin_bit_cast(bf16x8, f1);
-        pl[qb][0] = __builtin_bit_cast(bf16x8, g0);
-        pl[qb][1] = __builtin_bit_cast(bf16x8, g1);
-        l_run[qb] = l_run[qb] * alpha + psum;
-        m_run[qb] = m_new;
-        if (__any(alpha != 1.f)) {
-#pragma unroll
-          for (int db = 0; db < C::kDBlocks; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
-        }
+    for (int r = 0; r < 16; ++r) {
+      float v = sacc[r];
+      if (need_mask) {
+        const int pos = tok0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        const bool ok = pos < ctx || (pos < L && ((my_anc >> ((pos - ctx) & 63)) & 1ull));
+        v = ok ? v : -INFINITY;
+        sacc[r] = v;
       }
+      tmax = fmaxf(tmax, v);
     }
-
-    // ---- O^T += V^T P^T ----
+    tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    const float m_new = fmaxf(m_run, tmax);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_safe);
+    if (__any(alpha != 1.f)) {
 #pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db) {
-      const int d = 32 * db + ln;
-      const int vrow = (d & 7) * 18 + (d >> 3);
+      for (int db = 0; db < C::kDBlocks; ++db)
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+    // ---- P^T as two bf16 terms (value + rounding residual), 16 tokens at a time; O^T += V^T P^T ----
+    // A single bf16 rounding of P (2^-9 relative) would dominate the output error; carrying the
+    // rounding residual in a second bf16 term keeps ~16 bits of every weight.
+    float psum = 0.f;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      u32x4 hi, lo;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float p0 = fast_exp2(fmaf(sacc[8 * s + 2 * j], P.c, -m_safe));
+        const float p1 = fast_exp2(fmaf(sacc[8 * s + 2 * j + 1], P.c, -m_safe));
+        psum += p0 + p1;
+        const uint32_t h = pack_bf16(p0, p1);
+        hi[j] = h;
+        lo[j] = pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
+      }
+      const bf16x8 phi = __builtin_bit_cast(bf16x8, hi), plo = __builtin_bit_cast(bf16x8, lo);
+#pragma unroll
+      for (int db = 0; db < C::kDBlocks; ++db) {
+        const int d = 32 * db + ln;
+        const int vrow = (d & 7) * 18 + (d >> 3);
         const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(v_lds + vrow * C::kVStride + 32 * s + 16 * lh));
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-          if (qb < nqb) {
-            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qb][s], oacc[qb][db], 0, 0, 0);
-            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl[qb][s], oacc[qb][db], 0, 0, 0);
-          }
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, phi, oacc[db], 0, 0, 0);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plo, oacc[db], 0, 0, 0);
       }
     }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
     wave_lds_fence();
+    const long long prof_c = PROF_T();
+    prof_store += prof_b - prof_a;
+    prof_compute += prof_c - prof_b;
+    prof_tiles += 1;
   }
+  const long long prof_t1 = PROF_T();
 
-  // ---- merge the four waves ----
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32, kWave);
+  // ---- merge the waves that share a query block ----
+  l_run += __shfl_xor(l_run, 32, kWave);
   __syncthreads();                         // every wave is done with its tile memory
   if (lane < 32) {
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      sh_m[wave * NQB * 32 + qb * 32 + lane] = m_run[qb];
-      sh_l[wave * NQB * 32 + qb * 32 + lane] = l_run[qb];
-    }
+    sh_m[wave * 32 + lane] = m_run;
+    sh_l[wave * 32 + lane] = l_run;
   }
   __syncthreads();
-  float fscale[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, sh_m[w * NQB * 32 + qb * 32 + ln]);
-    float Ls = 0.f;
-#pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) {
-      const float mw = sh_m[w * NQB * 32 + qb * 32 + ln];
-      if (mw != -INFINITY) Ls += sh_l[w * NQB * 32 + qb * 32 + ln] * fast_exp2(mw - M);
-    }
-    fscale[qb] = (m_run[qb] == -INFINITY) ? 0.f : fast_exp2(m_run[qb] - M);
-    if (wave == 0 && lane < 32) {
-      sh_M[qb * 32 + lane] = M;
-      sh_L[qb * 32 + lane] = Ls;
-    }
-  }
+  float M = -INFINITY;
+  for (int s = 0; s < nslice; ++s) M = fmaxf(M, sh_m[(my_qb + nqbp * s) * 32 + ln]);
+  const float fscale = (m_run == -INFINITY) ? 0.f : fast_exp2(m_run - M);
 
-  float* sh_o = reinterpret_cast<float*>(smem);        // [4][32][kORedStride]
-  const int rn = tid >> 3;                               // query column this thread finalises
-  const int rd0 = (tid & 7) * (D / 8);                   // first of its D/8 dims
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    if (qb >= nqb) break;
-    __syncthreads();
+  float* sh_o = reinterpret_cast<float*>(smem);        // [4 waves][32][kORedStride]
+  if (wave_active) {
 #pragma unroll
     for (int db = 0; db < C::kDBlocks; ++db) {
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         float4 v;
-        v.x = oacc[qb][db][4 * r4 + 0] * fscale[qb];
-        v.y = oacc[qb][db][4 * r4 + 1] * fscale[qb];
-        v.z = oacc[qb][db][4 * r4 + 2] * fscale[qb];
-        v.w = oacc[qb][db][4 * r4 + 3] * fscale[qb];
+        v.x = oacc[db][4 * r4 + 0] * fscale;
+        v.y = oacc[db][4 * r4 + 1] * fscale;
+        v.z = oacc[db][4 * r4 + 2] * fscale;
+        v.w = oacc[db][4 * r4 + 3] * fscale;
         const int d = 32 * db + 8 * r4 + 4 * lh;
         *reinterpret_cast<float4*>(sh_o + (wave * 32 + ln) * C::kORedStride + d) = v;
       }
     }
-    __syncthreads();
-    const int row = row0 + 32 * qb + rn;
-    if (row < R) {
-      float acc[D / 8];
+  }
+  __syncthreads();
+  const int rn = tid >> 3;                               // query column this thread finalises
+  const int rd0 = (tid & 7) * (D / 8);                   // first of its D/8 dims
+  for (int qb = 0; qb < nqb; ++qb) {
+    const int orow = row0 + 32 * qb + rn;
+    if (orow >= R) continue;
+    float Mq = -INFINITY;
+    for (int s = 0; s < nslice; ++s) Mq = fmaxf(Mq, sh_m[(qb + nqbp * s) * 32 + rn]);
+    float Ls = 0.f;
+    float acc[D / 8];
 #pragma unroll
-      for (int i = 0; i < D / 8; ++i) acc[i] = 0.f;
+    for (int i = 0; i < D / 8; ++i) acc[i] = 0.f;
+    for (int s = 0; s < nslice; ++s) {
+      const int w = qb + nqbp * s;
+      const float mw = sh_m[w * 32 + rn];
+      if (mw != -INFINITY) Ls += sh_l[w * 32 + rn] * fast_exp2(mw - Mq);
 #pragma unroll
-      for (int w = 0; w < kAttnWaves; ++w)
-#pragma unroll
-        for (int i = 0; i < D / 8; i += 4) {
-          const float4 v = *reinterpret_cast<const float4*>(sh_o + (w * 32 + rn) * C::kORedStride + rd0 + i);
-          acc[i] += v.x; acc[i + 1] += v.y; acc[i + 2] += v.z; acc[i + 3] += v.w;
-        }
-      const int node = row / P.G, g = row % P.G;
-      const int64_t grow = static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + g;
-      const float M = sh_M[qb * 32 + rn], Ls = sh_L[qb * 32 + rn];
-      if (nchunks == 1) {
-        const float inv = 1.f / Ls;
-        if (P.out_f32) {
-          float* o = static_cast<float*>(P.out) + grow * D + rd0;
-#pragma unroll
-          for (int i = 0; i < D / 8; ++i) o[i] = acc[i] * inv;
-        } else {
-          uint32_t* o = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(P.out) + grow * D + rd0);
-#pragma unroll
-          for (int i = 0; i < D / 16; ++i) o[i] = pack_bf16(acc[2 * i] * inv, acc[2 * i + 1] * inv);
-        }
-        if (P.lse && (tid & 7) == 0) P.lse[grow] = (M + log2f(Ls)) * static_cast<float>(kLn2);
-      } else {
-        float* o = P.ws_o + (grow * P.max_chunks + chunk) * D + rd0;
-#pragma unroll
-        for (int i = 0; i < D / 8; ++i) o[i] = acc[i];
-        if ((tid & 7) == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(M, Ls);
+      for (int i = 0; i < D / 8; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(sh_o + (w * 32 + rn) * C::kORedStride + rd0 + i);
+        acc[i] += v.x; acc[i + 1] += v.y; acc[i + 2] += v.z; acc[i + 3] += v.w;
       }
     }
+    const int onode = orow / P.G, og = orow % P.G;
+    const int64_t grow = static_cast<int64_t>(q0 + onode) * P.Hq + kvh * P.G + og;
+    if (nchunks == 1) {
+      const float inv = 1.f / Ls;
+      if (P.out_f32) {
+        float* o = static_cast<float*>(P.out) + grow * D + rd0;
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) o[i] = acc[i] * inv;
+      } else {
+        uint32_t* o = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(P.out) + grow * D + rd0);
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i) o[i] = pack_bf16(acc[2 * i] * inv, acc[2 * i + 1] * inv);
+      }
+      if (P.lse && (tid & 7) == 0) P.lse[grow] = (Mq + log2f(Ls)) * static_cast<float>(kLn2);
+    } else {
+      float* o = P.ws_o + (grow * P.max_chunks + chunk) * D + rd0;
+#pragma unroll
+      for (int i = 0; i < D / 8; ++i) o[i] = acc[i];
+      if ((tid & 7) == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(Mq, Ls);
+    }
   }
+  PROF_ADD(0, 1);
+  PROF_ADD(1, prof_t1 - prof_t0);
+  PROF_ADD(2, prof_store);
+  PROF_ADD(3, prof_compute);
+  PROF_ADD(4, prof_tiles);
+  PROF_ADD(5, PROF_T() - prof_t1);
+  (void)prof_t0; (void)prof_t1; (void)prof_store; (void)prof_compute; (void)prof_tiles;
 }
 
 // ----------------------------------------------------------------------------------
@@ -549,7 +551,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   const int vc = tid % RC::kCh;                 // V: 16-byte chunk of the token row
   const int vg = tid / RC::kCh;                 // V: group of kTpt consecutive tokens
   const int vtok0 = vg * RC::kTpt;              // first of them within the tile
-  u32x4 kr[RC::kLoads], vr[RC::kLoads];
+  // two register sets: while tile t is computed from LDS, tile t+1 waits in one set and tile
+  // t+2 is in flight into the other, i.e. two tiles of global loads are outstanding per workgroup
+  u32x4 krA[RC::kLoads], vrA[RC::kLoads], krB[RC::kLoads], vrB[RC::kLoads];
 
   // Page ids of the whole chunk go to LDS once, so that the tile loads depend on no global read.
   const int lp0 = t_begin / kPage;
@@ -566,7 +570,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   const int k_lane_off = (k_tok_in_load % kPage) * D + (tid % RC::kCh) * 8;
   const int k_page_in_load = k_tok_in_load / kPage;                   // wave-uniform
   const int v_lane_off = (vtok0 % kPage) * D + vc * 8;
-  auto issue_loads = [&](int t) {
+  auto issue_loads = [&](int t, u32x4 (&kr)[RC::kLoads], u32x4 (&vr)[RC::kLoads]) {
 #pragma unroll
     for (int j = 0; j < RC::kLoads; ++j) {
       const int pidx = (RC::kT * t + j * kTokPerLoadWg) / kPage + k_page_in_load;
@@ -580,7 +584,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     for (int i = 0; i < RC::kTpt; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vp + i * D);
   };
 
-  auto store_tile = [&](int stage, int t) {
+  auto store_tile = [&](int stage, int t, u32x4 (&kr)[RC::kLoads], u32x4 (&vr)[RC::kLoads]) {
     unsigned char* k_lds = smem + stage * RC::kStage;
     unsigned char* v_lds = k_lds + RC::kKBytes;
 #pragma unroll
@@ -688,15 +692,25 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   };
 
   // ---- pipeline: tile t is computed from LDS while tile t+1 sits in registers ----
-  issue_loads(0);
-  store_tile(0, 0);
-  if (ntiles > 1) issue_loads(1);
+  issue_loads(0, krA, vrA);
+  if (ntiles > 1) issue_loads(1, krB, vrB);
+  store_tile(0, 0, krA, vrA);
+  if (ntiles > 2) issue_loads(2, krA, vrA);
   __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
-    if (active) compute_tile(t & 1, t);
+  for (int t = 0; t < ntiles; t += 2) {
+    // LDS stage 0 holds tile t, set B tile t+1, set A tile t+2
+    if (active) compute_tile(0, t);
     if (t + 1 < ntiles) {
-      store_tile((t + 1) & 1, t + 1);
-      if (t + 2 < ntiles) issue_loads(t + 2);
+      store_tile(1, t + 1, krB, vrB);
+      if (t + 3 < ntiles) issue_loads(t + 3, krB, vrB);
+    }
+    __syncthreads();
+    if (t + 1 >= ntiles) break;
+    // LDS stage 1 holds tile t+1, set A tile t+2, set B tile t+3
+    if (active) compute_tile(1, t + 1);
+    if (t + 2 < ntiles) {
+      store_tile(0, t + 2, krA, vrA);
+      if (t + 4 < ntiles) issue_loads(t + 4, krA, vrA);
     }
     __syncthreads();
   }
@@ -802,9 +816,15 @@ static AttnPlan make_plan(const AttnArgs& a) {
   AttnPlan p;
   const int G = a.Hq / a.Hkv;
   const int max_rows = a.max_q * G;
-  if (max_rows <= 32) { p.kind = 0; p.rows_per_wg = 32; }
-  else if (max_rows <= 128 || a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
+  if (max_rows <= 128) { p.kind = 0; p.rows_per_wg = 128; }
+  else if (a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
   else { p.kind = 2; p.rows_per_wg = 256; }
+  if (const char* e = getenv("SPECV_ATTN_KIND")) {      // development knob: force a kernel family
+    const int k = atoi(e);
+    if (k == 1) { p.kind = 1; p.rows_per_wg = 128; }
+    if (k == 2 && a.D == 128) { p.kind = 2; p.rows_per_wg = 256; }
+    if (k == 0) { p.kind = 0; p.rows_per_wg = 128; }
+  }
   p.row_groups = (max_rows + p.rows_per_wg - 1) / p.rows_per_wg;
   const int gran = p.kind == 0 ? kTile : 64;              // chunks are whole tiles
   const int64_t max_tok = static_cast<int64_t>(a.max_pages) * a.page;
@@ -849,13 +869,13 @@ static int set_lds_once(K kernel, size_t lds, bool& done) {
 template <int D>
 static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
   using C = AttnCfg<D>;
-  constexpr size_t kMerge = kAttnWaves * 32 * C::kORedStride * sizeof(float) + (2 * kAttnWaves + 2) * 32 * sizeof(float);
+  constexpr size_t kMerge = kAttnWaves * 32 * C::kORedStride * sizeof(float) + 2 * kAttnWaves * 32 * sizeof(float);
   constexpr size_t kTiles = static_cast<size_t>(kAttnWaves) * C::kWaveLds;
   static_assert(kMerge <= kTiles, "merge buffers must fit in the tile memory");
   static bool attr_done = false;
-  if (set_lds_once(&attn_stream_kernel<D, 1>, kTiles, attr_done) != 0) return -6;
+  if (set_lds_once(&attn_stream_kernel<D>, kTiles, attr_done) != 0) return -6;
   dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
-  hipLaunchKernelGGL((attn_stream_kernel<D, 1>), grid, dim3(kAttnThreads), kTiles, stream, P);
+  hipLaunchKernelGGL((attn_stream_kernel<D>), grid, dim3(kAttnThreads), kTiles, stream, P);
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
@@ -902,3 +922,14 @@ int launch_attn(const AttnArgs& a, hipStream_t stream) {
 }
 
 }  // namespace specv
+
+#ifdef SPECV_PROFILE
+extern "C" void spec_debug_read_prof(unsigned long long* out8, int reset) {
+  (void)hipMemcpyFromSymbol(out8, HIP_SYMBOL(specv::g_prof), 8 * sizeof(unsigned long long));
+  if (reset) {
+    unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    (void)hipMemcpyToSymbol(HIP_SYMBOL(specv::g_prof), z, sizeof z);
+  }
+}
+#endif
+
