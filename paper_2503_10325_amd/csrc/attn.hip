@@ -305,7 +305,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
       float v = sacc[r];
       if (need_mask) {
         const int pos = tok0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-        const bool ok = pos < ctx || (pos < L && ((my_anc >> ((pos - ctx) & 63)) & 1ull));
+        // branch-free on purpose: bitwise ops, no short-circuit control flow around the accumulator
+          const bool ok = (pos < ctx) | ((pos < L) & (((my_anc >> ((pos - ctx) & 63)) & 1ull) != 0ull));
         v = ok ? v : -INFINITY;
         sacc[r] = v;
       }
@@ -623,72 +624,117 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     }
   };
 
+  // One 64-token tile = one online-softmax step.  Program order is pinned (sched_barrier) so that
+  // LDS operand reads run two steps ahead of the MFMAs that consume them and the exponentials of
+  // the next 16 tokens are computed while the PV MFMAs of the current 16 tokens execute.
   auto compute_tile = [&](int stage, int t) {
     const unsigned char* k_lds = smem + stage * RC::kStage;
     const unsigned char* v_lds = k_lds + RC::kKBytes;
-#pragma unroll 1
-    for (int tb = 0; tb < RC::kT / 32; ++tb) {
-      const int tok0 = t_begin + RC::kT * t + 32 * tb;
-      if (tok0 >= t_end) break;
-      f32x16 sacc;
+    const int tok0 = t_begin + RC::kT * t;
+    const unsigned char* k_rd = k_lds + ln * RC::kKStride + 16 * lh;
+    auto k_frag = [&](int ks, int tb) {
+      return as_bf16x8(*reinterpret_cast<const u32x4*>(k_rd + 32 * tb * RC::kKStride + 32 * ks));
+    };
+    f32x16 sacc[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+    for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-      for (int ks = 0; ks < C::kQKSteps; ++ks) {
-        const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(k_lds + (32 * tb + ln) * RC::kKStride + 32 * ks + 16 * lh));
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
+      for (int r = 0; r < 16; ++r) sacc[tb][r] = 0.f;
+    // three operand slots in rotation: the slot refilled at step ks was last read by the MFMAs
+    // of step ks-1, never by the ones just issued
+    bf16x8 ka[3][2];
+    ka[0][0] = k_frag(0, 0); ka[0][1] = k_frag(0, 1);
+    ka[1][0] = k_frag(1, 0); ka[1][1] = k_frag(1, 1);
+#pragma unroll
+    for (int ks = 0; ks < C::kQKSteps; ++ks) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 2 < C::kQKSteps) {
+        ka[(ks + 2) % 3][0] = k_frag(ks + 2, 0);
+        ka[(ks + 2) % 3][1] = k_frag(ks + 2, 1);
       }
-      const bool need_mask = tok0 + 32 > ctx;
-      float tmax = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = sacc[r];
-        if (need_mask) {
-          const int pos = tok0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          const bool ok = pos < ctx || (pos < L && ((my_anc >> ((pos - ctx) & 63)) & 1ull));
-          v = ok ? v : -INFINITY;
-          sacc[r] = v;
-        }
-        tmax = fmaxf(tmax, v);
-      }
-      tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-      const float m_new = fmaxf(m_run, tmax);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run - m_safe);
-      if (__any(alpha != 1.f)) {
-#pragma unroll
-        for (int db = 0; db < C::kDBlocks; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-      }
-      // P^T in two bf16 terms (hi + rounding residual), 16 tokens at a time, fed straight to PV
-      float psum = 0.f;
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        u32x4 hi, lo;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float p0 = fast_exp2(fmaf(sacc[8 * s + 2 * j], P.c, -m_safe));
-          const float p1 = fast_exp2(fmaf(sacc[8 * s + 2 * j + 1], P.c, -m_safe));
-          psum += p0 + p1;
-          const uint32_t h = pack_bf16(p0, p1);
-          hi[j] = h;
-          lo[j] = pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
-        }
-        const bf16x8 phi = __builtin_bit_cast(bf16x8, hi), plo = __builtin_bit_cast(bf16x8, lo);
-#pragma unroll
-        for (int db = 0; db < C::kDBlocks; ++db) {
-          const int d = 32 * db + ln;
-          const int vrow = (d & 7) * 18 + (d >> 3);
-          const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(v_lds + vrow * RC::kVStride + 64 * tb + 32 * s + 16 * lh));
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, phi, oacc[db], 0, 0, 0);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plo, oacc[db], 0, 0, 0);
-        }
-      }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
+      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % 3][0], qf[ks], sacc[0], 0, 0, 0);
+      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % 3][1], qf[ks], sacc[1], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // V^T operand of the first 16 tokens is fetched while the scores are reduced
+    const unsigned char* v_rd = v_lds + ((ln & 7) * 18 + (ln >> 3)) * RC::kVStride + 16 * lh;
+    auto v_frag = [&](int chunk, int db) {      // chunk = 16-token group 0..3 of the tile
+      return as_bf16x8(*reinterpret_cast<const u32x4*>(v_rd + 4 * db * RC::kVStride + 32 * chunk));
+    };
+    bf16x8 va[C::kDBlocks];
+#pragma unroll
+    for (int db = 0; db < C::kDBlocks; ++db) va[db] = v_frag(0, db);
+
+    if (tok0 + RC::kT > ctx) {                   // tile reaches the drafts or the end: apply the mask
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int pos = tok0 + 32 * tb + 8 * (r >> 2) + 4 * lh + (r & 3);
+          // branch-free on purpose: bitwise ops, no short-circuit control flow around the accumulator
+          const bool ok = (pos < ctx) | ((pos < L) & (((my_anc >> ((pos - ctx) & 63)) & 1ull) != 0ull));
+          sacc[tb][r] = ok ? sacc[tb][r] : -INFINITY;
+        }
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[tb][r]);
+    tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    const float m_new = fmaxf(m_run, tmax);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_safe);
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+    // P^T in two bf16 terms (value + rounding residual), 16 tokens at a time
+    float psum = 0.f;
+    auto p_chunk = [&](int chunk, bf16x8& phi, bf16x8& plo) {
+      const int tb = chunk >> 1, s = chunk & 1;
+      u32x4 hi, lo;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float p0 = fast_exp2(fmaf(sacc[tb][8 * s + 2 * j], P.c, -m_safe));
+        const float p1 = fast_exp2(fmaf(sacc[tb][8 * s + 2 * j + 1], P.c, -m_safe));
+        psum += p0 + p1;
+        const uint32_t h = pack_bf16(p0, p1);
+        hi[j] = h;
+        lo[j] = pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
+      }
+      phi = __builtin_bit_cast(bf16x8, hi);
+      plo = __builtin_bit_cast(bf16x8, lo);
+    };
+    bf16x8 phi, plo;
+    p_chunk(0, phi, plo);
+#pragma unroll
+    for (int chunk = 0; chunk < 4; ++chunk) {
+      __builtin_amdgcn_sched_barrier(0);
+      bf16x8 vn[C::kDBlocks];
+      if (chunk + 1 < 4) {
+#pragma unroll
+        for (int db = 0; db < C::kDBlocks; ++db) vn[db] = v_frag(chunk + 1, db);
+      }
+#pragma unroll
+      for (int db = 0; db < C::kDBlocks; ++db) {
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], phi, oacc[db], 0, 0, 0);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], plo, oacc[db], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (chunk + 1 < 4) {
+        bf16x8 nhi, nlo;
+        p_chunk(chunk + 1, nhi, nlo);          // VALU work in the shadow of the MFMAs just issued
+        phi = nhi; plo = nlo;
+#pragma unroll
+        for (int db = 0; db < C::kDBlocks; ++db) va[db] = vn[db];
+      }
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
   };
 
   // ---- pipeline: tile t is computed from LDS while tile t+1 sits in registers ----
