@@ -851,7 +851,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P, int tot
 // host side
 // ----------------------------------------------------------------------------------
 struct AttnPlan {
-  int kind;           // 0: token-split kernel (<= 32 rows per KV head), 1: row-split, 4 waves, 2: row-split, 8 waves
+  int kind;           // 0: token-split kernel (<= 128 rows per KV head), 1: row-split, 4 waves, 2: row-split, 8 waves
   int rows_per_wg;
   int row_groups;
   int chunk_tokens;
@@ -872,21 +872,30 @@ static AttnPlan make_plan(const AttnArgs& a) {
     if (k == 0) { p.kind = 0; p.rows_per_wg = 128; }
   }
   p.row_groups = (max_rows + p.rows_per_wg - 1) / p.rows_per_wg;
-  const int gran = p.kind == 0 ? kTile : 64;              // chunks are whole tiles
+  const bool token_split = (p.kind == 0);
+  const int gran = token_split ? kTile : 64;              // chunks are whole tiles
   const int64_t max_tok = static_cast<int64_t>(a.max_pages) * a.page;
   int64_t tok = a.kv_hint > 0 ? a.kv_hint : static_cast<int64_t>(a.B) * max_tok;
-  // Workgroups to aim for.  Each one pays a fixed prologue/epilogue, so uniform batches want
-  // about one per compute unit; ragged ones need more for the dispatcher to balance lengths.
-  int64_t jobs_target = p.kind == 0 ? 256 : 512;
+  // Chunk length.  Every workgroup pays a fixed prologue/epilogue (and, when a request is split, a
+  // partial-result round trip proportional to its query rows), so chunks are as long as two
+  // limits allow: (a) about one workgroup per compute unit should exist, (b) one wave should not
+  // stream more than ~40 tiles in sequence, or the longest workgroup sets the kernel's duration.
+  int64_t jobs_target = 256;
   if (const char* e = getenv("SPECV_ATTN_JOBS")) {      // development knob for sweeps
     const long v = atol(e);
     if (v > 0) jobs_target = v;
   }
   int64_t chunk = (tok * a.Hkv * p.row_groups + jobs_target - 1) / jobs_target;
+  if (token_split && !getenv("SPECV_ATTN_JOBS")) {
+    // waves that share one query block (pair) and therefore split its tiles
+    const int nslice = max_rows <= 32 ? 4 : (max_rows <= 64 ? 2 : 1);
+    const int64_t cap = static_cast<int64_t>(40) * kTile * nslice;
+    if (chunk > cap) chunk = cap;
+  }
   if (chunk < 256) chunk = 256;
   chunk = (chunk + gran - 1) / gran * gran;
   if (chunk > max_tok) chunk = (max_tok + gran - 1) / gran * gran;
-  if (p.kind != 0 && chunk > 16384) chunk = 16384;          // the row-split kernel keeps a chunk's page ids in LDS
+  if (!token_split && chunk > 16384) chunk = 16384;          // the row-split kernel keeps a chunk's page ids in LDS
   if (chunk < gran) chunk = gran;
   p.chunk_tokens = static_cast<int>(chunk);
   p.max_chunks = static_cast<int>((max_tok + chunk - 1) / chunk);
