@@ -133,27 +133,27 @@ struct WalkRows {
 // The weight of level L is w_L (unnormalised; p itself at level 0).  Per-class values are
 // fp32 (their relative error, ~1e-7, is that of the hardware exp2 anyway); every sum over
 // classes is carried in fp64.
-__device__ __forceinline__ float level_weight(float p, float q, int L, const float* __restrict__ inv_R) {
-  float r = p;
-  for (int k = 0; k < L; ++k) {
-    const float w = fmaxf(r - q, 0.f);
-    r = (k + 1 < L) ? w * inv_R[k] : w;      // the last level stays unnormalised
-  }
-  return r;
-}
-
 // Weights of eight consecutive token classes from their logits (q: logits or probabilities).
+// The level loop is outermost so that its (wave-uniform) trip count is tested once per eight classes;
+// the last level stays unnormalised (scale 1, exact).
 __device__ __forceinline__ void weights_from(const WalkRows& R, const float (&lp)[8], const float (&lq)[8],
                                              int n_valid, float c, int L, const float* __restrict__ inv_R,
                                              float (&w)[8]) {
   const float t_invz = static_cast<float>(R.t_invz), q_invz = static_cast<float>(R.q_invz);
+  float q[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const float p = fast_exp2((lp[j] - R.t_m) * c) * t_invz;
-    float q = 0.f;
-    if (L > 0) q = R.q_is_probs ? lq[j] : fast_exp2((lq[j] - R.q_m) * c) * q_invz;
-    w[j] = (j < n_valid) ? level_weight(p, q, L, inv_R) : 0.f;
+    w[j] = fast_exp2((lp[j] - R.t_m) * c) * t_invz;
+    q[j] = 0.f;
+    if (L > 0) q[j] = R.q_is_probs ? lq[j] : fast_exp2((lq[j] - R.q_m) * c) * q_invz;
   }
+  for (int k = 0; k < L; ++k) {
+    const float scale = (k + 1 < L) ? inv_R[k] : 1.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[j] = fmaxf(w[j] - q[j], 0.f) * scale;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) w[j] = (j < n_valid) ? w[j] : 0.f;
 }
 
 template <bool VEC>
@@ -467,16 +467,16 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       int found = -1;
       if (cross) {
         const int fl = __ffsll(static_cast<long long>(cross)) - 1;
+        // every lane works out its own candidate: no lane-dependent branch ahead of the broadcast
+        // (with one, the compiler may let lanes reach the broadcast without the lane they read from)
         int tok = -1;
-        if (lane == fl) {
-          double acc = run + inc - ls;
+        double acc = run + inc - ls;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            acc += static_cast<double>(w[j]);
-            if (tok < 0 && acc > target && w[j] > 0.f) tok = e0 + j;
-          }
-          if (tok < 0) tok = my_last;      // rounding inside the lane: its last positive class
+        for (int j = 0; j < 8; ++j) {
+          acc += static_cast<double>(w[j]);
+          if (tok < 0 && acc > target && w[j] > 0.f) tok = e0 + j;
         }
+        if (tok < 0) tok = my_last;        // rounding inside the lane: its last positive class
         found = __shfl(tok, fl, kWave);
       }
       if (found < 0) {                     // rounding across lanes: last positive class of the block
