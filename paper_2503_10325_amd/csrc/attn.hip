@@ -210,39 +210,43 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
   u32x4 kr[C::kLoads], vr[C::kLoads];
 
   // Page ids are fetched one tile ahead of the K/V loads that need them, so the tile loads never
-  // wait on a dependent block-table read.
-  int pg[2] = {-1, -1};
+  // wait on a dependent block-table read.  They are wave-uniform: the loads below take the page
+  // base from scalar registers and add a per-lane byte offset that never changes, so a tile costs
+  // no address arithmetic and no branch.  Ids past the request's last page repeat the last page and
+  // negative ids read page 0: the data is in bounds, and tokens at or beyond L are masked (K) or
+  // zeroed before they reach LDS (V).
+  const int last_page = (L - 1) / kPage;
+  int pg[2] = {0, 0};
   auto fetch_pages = [&](int t) {
     if (t < ntiles) {
-      const int tok0 = t_begin + kTile * t;
-      const int lp = tok0 / kPage;
+      const int lp = (t_begin + kTile * t) / kPage;
       pg[0] = bt[lp];
-      pg[1] = (tok0 + kPage < L) ? bt[lp + 1] : -1;
+      pg[1] = bt[min(lp + 1, last_page)];
     }
   };
+  const unsigned k_lane_off = static_cast<unsigned>(kt * D + kc * 8) * 2u;            // bytes
+  const unsigned v_lane_off = static_cast<unsigned>(4 * va * D + kc * 8) * 2u;
+  const int64_t page_bytes = page_elems * 2, head_bytes = head_off * 2;
   auto issue_loads = [&](int t) {
-    const int tok0 = t_begin + kTile * t;
+    const int p0 = max(__builtin_amdgcn_readfirstlane(pg[0]), 0);
+    const int p1 = max(__builtin_amdgcn_readfirstlane(pg[1]), 0);
+    const int64_t o0 = p0 * page_bytes + head_bytes, o1 = p1 * page_bytes + head_bytes;
+    const unsigned char* kb[2] = {reinterpret_cast<const unsigned char*>(P.k_pool) + o0,
+                                  reinterpret_cast<const unsigned char*>(P.k_pool) + o1};
+    const unsigned char* vb[2] = {reinterpret_cast<const unsigned char*>(P.v_pool) + o0,
+                                  reinterpret_cast<const unsigned char*>(P.v_pool) + o1};
 #pragma unroll
     for (int j = 0; j < C::kLoads; ++j) {
-      const int tk = j * C::kTokPerLoad + kt;
-      const int page = pg[(j * C::kTokPerLoad) / kPage];
-      u32x4 v = zero4();
-      if (page >= 0)
-        v = *reinterpret_cast<const u32x4*>(P.k_pool + page * page_elems + head_off + (tk % kPage) * D + kc * 8);
-      kr[j] = v;
+      constexpr int kRowBytes = D * 2;
+      const int tk0 = j * C::kTokPerLoad;                 // first token row of this load (compile time)
+      kr[j] = *reinterpret_cast<const u32x4*>(kb[tk0 / kPage] + k_lane_off + (tk0 % kPage) * kRowBytes);
     }
 #pragma unroll
     for (int pi = 0; pi < C::kVPageIters; ++pi) {
-      const int s = pi * C::kPagesPerLoad + vs_lane;
-      const int page = pg[s];
+      // D = 128: one page per round (scalar base); D = 64: the two half-waves read the tile's two pages
+      const unsigned char* base = (C::kPagesPerLoad == 2) ? (vs_lane ? vb[1] : vb[0]) : vb[pi];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int slot = 4 * va + i;
-        u32x4 v = zero4();
-        if (page >= 0 && tok0 + kPage * s + slot < L)      // never multiply stale cache slots into O
-          v = *reinterpret_cast<const u32x4*>(P.v_pool + page * page_elems + head_off + slot * D + kc * 8);
-        vr[pi * 4 + i] = v;
-      }
+      for (int i = 0; i < 4; ++i) vr[pi * 4 + i] = *reinterpret_cast<const u32x4*>(base + v_lane_off + i * D * 2);
     }
   };
 
@@ -262,6 +266,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
       const int tk = j * C::kTokPerLoad + kt;
       *reinterpret_cast<u32x4*>(k_lds + tk * C::kKStride + kc * 16) = kr[j];
     }
+    const int tok0 = t_begin + kTile * t;
+    if (tok0 + kTile > L) {                  // last, partial tile: stale cache slots must not reach O
+#pragma unroll
+      for (int pi = 0; pi < C::kVPageIters; ++pi)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = tok0 + kPage * (pi * C::kPagesPerLoad + vs_lane) + 4 * va + i;
+          if (tok >= L) vr[pi * 4 + i] = zero4();
+        }
+    }
 #pragma unroll
     for (int pi = 0; pi < C::kVPageIters; ++pi) {
       const int s = pi * C::kPagesPerLoad + vs_lane;
@@ -279,7 +293,6 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
         }
       }
     }
-    const int tok0 = t_begin + kTile * t;
     if (t + nslice < ntiles) {
       issue_loads(t + nslice);
       fetch_pages(t + 2 * nslice);
