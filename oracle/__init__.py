@@ -160,3 +160,29 @@ def accept(node_offsets, parent, draft_tokens, target_logits, draft_q, q_row, u_
     if rc != 0:
         raise RuntimeError(f"oracle_accept failed: {rc}")
     return dict(accept_len=accept_len, out_tokens=out_tokens, stop_node=stop, ratio=ratio, near_tie=tie)
+
+
+def accept_greedy(node_offsets, parent, draft_tokens, target_logits, out_stride=None):
+    """Greedy verification.  Returns dict(accept_len [B], out_tokens [B,out_stride] (-1 padded),
+    stop_node [B], row_argmax [total + B])."""
+    node_offsets = _i32(node_offsets)
+    B = node_offsets.shape[0] - 1
+    total = int(node_offsets[-1])
+    par = None if parent is None else _i32(parent)
+    draft_tokens = _i32(draft_tokens)
+    tl, tdt = _logits(target_logits)
+    V = tl.shape[1]
+    assert tl.shape[0] == total + B and draft_tokens.shape[0] == total
+    n = np.diff(node_offsets)
+    if out_stride is None:
+        out_stride = int(n.max()) + 1 if B else 1
+    accept_len = np.zeros(B, dtype=np.int32)
+    out_tokens = np.full((B, out_stride), -1, dtype=np.int32)
+    stop = np.zeros(B, dtype=np.int32)
+    arg = np.zeros(total + B, dtype=np.int32)
+    rc = lib().oracle_accept_greedy(
+        ctypes.c_int(B), ctypes.c_int(V), _p(node_offsets), _p(par), _p(draft_tokens), _p(tl),
+        ctypes.c_int(tdt), _p(accept_len), _p(out_tokens), ctypes.c_int(out_stride), _p(stop), _p(arg))
+    if rc != 0:
+        raise RuntimeError(f"oracle_accept_greedy failed: {rc}")
+    return dict(accept_len=accept_len, out_tokens=out_tokens, stop_node=stop, row_argmax=arg)

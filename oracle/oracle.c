@@ -23,6 +23,11 @@
  *                         rest and a replacement is drawn from
  *                         norm(max(0, o_i - q_i)); if nothing is rejected one more
  *                         token is drawn from the target distribution.
+ *   oracle_accept_greedy - the same walk under greedy sampling, the decoding rule of
+ *                         the paper's experiments (Section 6.1, experiment settings):
+ *                         a draft token is kept when it is the target's most likely
+ *                         token at its position; the first mismatch is replaced by
+ *                         that most likely token.
  *
  * Pins: tests/test_oracle_*.py (closed forms, chi-square, brute force on tiny
  * vocabularies, library SDPA on the causal special case, tree/path equivalence).
@@ -321,4 +326,61 @@ int oracle_accept(int B, int V, const int32_t* node_offsets, const int32_t* pare
     free(qv);
   }
   return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* greedy verification                                                         */
+/* ------------------------------------------------------------------------- */
+/* Index of the largest logit of a row; the lowest index wins among equal values.
+ * A value replaces the running best only when strictly greater, so NaN entries
+ * never win and a row without any finite entry gives index 0. */
+static int argmax_row(const void* logits, int dtype, int64_t row, int V) {
+  double best = -INFINITY;
+  int idx = 0;
+  for (int v = 0; v < V; ++v) {
+    const double x = load_logit(logits, dtype, row * (int64_t)V + v);
+    if (x > best) { best = x; idx = v; }
+  }
+  return idx;
+}
+
+/*
+ * Greedy verification (Section 6.1: draft generation and verification both use
+ * greedy sampling).  Same inputs as oracle_accept without draft distributions or
+ * uniforms.  cur = committed prefix; g = argmax of the target row after cur.  The
+ * first child c of cur (index order) with draft_tokens[c] == g is accepted and the
+ * walk descends; when cur has no such child, g is emitted and the walk stops.
+ * row_argmax [total + B] (optional) receives the argmax of every target row.
+ */
+int oracle_accept_greedy(int B, int V, const int32_t* node_offsets, const int32_t* parent,
+                         const int32_t* draft_tokens, const void* target_logits, int tdt,
+                         int32_t* accept_len, int32_t* out_tokens, int out_stride,
+                         int32_t* stop_node, int32_t* row_argmax) {
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    const int o = node_offsets[b];
+    const int n = node_offsets[b + 1] - o;
+    const int64_t trow0 = (int64_t)o + b;
+    if (row_argmax)
+      for (int i = 0; i <= n; ++i) row_argmax[trow0 + i] = argmax_row(target_logits, tdt, trow0 + i, V);
+    int cur = -1, depth = 0;
+    for (;;) {
+      const int g = argmax_row(target_logits, tdt, trow0 + 1 + cur, V);
+      int accepted_child = -1;
+      for (int c = cur + 1; c < n; ++c) {
+        const int pc = parent ? parent[o + c] : c - 1;
+        if (pc == cur && draft_tokens[o + c] == g) { accepted_child = c; break; }
+      }
+      if (accepted_child < 0) {
+        if (depth < out_stride) out_tokens[(int64_t)b * out_stride + depth] = g;
+        break;
+      }
+      if (depth < out_stride) out_tokens[(int64_t)b * out_stride + depth] = g;
+      ++depth;
+      cur = accepted_child;
+    }
+    accept_len[b] = depth;
+    if (stop_node) stop_node[b] = cur;
+  }
+  return 0;
 }
