@@ -178,6 +178,39 @@ int32_t spec_accept(
                                     node, NaN where not visited                         */
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------
+ * spec_accept_greedy
+ *
+ * The same walk under greedy sampling, the decoding rule of the paper's experiments
+ * (Section 6.1, experiment settings: greedy sampling for draft generation and
+ * verification).  Target rows are laid out as for spec_accept.  g = index of the
+ * largest logit of the current node's target row (ordinary fp32 comparison, -0 equal
+ * to +0, NaN never the largest; the lowest index among equal values; a row without
+ * any comparable entry gives 0).  The first child c of the current node, in index
+ * order, with draft_tokens[c] == g is accepted and the walk descends; when there is
+ * none, g is emitted and the walk stops.  No draft distributions, no uniforms, no
+ * temperature: the result is exact integer work.  Rows (total_nodes + B) are limited
+ * to 65535 per call; bad parent entries (>= own index or < -1) count as -1.
+ * ---------------------------------------------------------------------------- */
+size_t spec_accept_greedy_workspace_size(int32_t B, int32_t total_nodes, int32_t V);
+
+int32_t spec_accept_greedy(
+    int32_t B, int32_t V,
+    int32_t total_nodes,         /* = node_offsets[B] (host copy)                      */
+    int32_t max_nodes_per_req,   /* upper bound of n[b]; at most 64                    */
+    const int32_t* node_offsets, /* [B+1]                                              */
+    const int32_t* parent,       /* [total_nodes] or NULL = linear chain               */
+    const int32_t* draft_tokens, /* [total_nodes]                                      */
+    const void* target_logits,   /* [total_nodes + B, V]                               */
+    int32_t target_dtype,        /* spec_dtype                                         */
+    int32_t* accept_len,         /* [B] number of accepted draft tokens                */
+    int32_t* out_tokens,         /* [B, out_stride]: accepted tokens, then the emitted one;
+                                    entries past accept_len[b]+1 are set to -1          */
+    int32_t out_stride,          /* >= max_nodes_per_req + 1                           */
+    int32_t* stop_node,          /* optional [B]: last accepted node or -1             */
+    int32_t* row_argmax,         /* optional [total_nodes + B]: g of every target row  */
+    void* workspace, size_t workspace_bytes, void* stream);
+
 const char* spec_strerror(int32_t status);
 
 /* Library/ABI version, bumped when a signature changes. */

@@ -22,6 +22,7 @@ EXPORTS = [
     "spec_verify_attn_workspace_size", "spec_verify_attn",
     "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
     "spec_accept_workspace_size", "spec_accept",
+    "spec_accept_greedy_workspace_size", "spec_accept_greedy",
     "spec_strerror", "spec_abi_version",
 ]
 
@@ -65,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.spec_fuse_drafts.argtypes = [i32] * 4 + [vp] * 4 + [i32, f32, i32] + [vp] * 5 + [sz, vp]
         L.spec_accept_workspace_size.restype = sz
         L.spec_accept_workspace_size.argtypes = [i32] * 4
+        L.spec_accept_greedy_workspace_size.restype = sz
+        L.spec_accept_greedy_workspace_size.argtypes = [i32] * 3
+        L.spec_accept_greedy.restype = i32
+        L.spec_accept_greedy.argtypes = [i32] * 4 + [vp] * 4 + [i32, vp, vp, i32, vp, vp, vp, sz, vp]
         L.spec_accept.restype = i32
         L.spec_accept.argtypes = ([i32] * 5 + [vp] * 4 + [i32, vp, i32, i32, vp, f32] + [vp] * 4 + [i32]
                                   + [vp] * 3 + [sz, vp])
@@ -162,3 +167,20 @@ def spec_accept(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_t
                            _ptr(workspace), ws_bytes, _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_accept", rc)
+
+
+def spec_accept_greedy_workspace_size(B, total_nodes, V) -> int:
+    return int(lib().spec_accept_greedy_workspace_size(B, total_nodes, V))
+
+
+def spec_accept_greedy(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_tokens, target_logits,
+                       accept_len, out_tokens, stop_node=None, row_argmax=None, workspace=None, stream=None) -> None:
+    """target_logits [total_nodes+B, V] (bf16 or fp32 device tensor); out_tokens [B, out_stride] int32."""
+    V = target_logits.shape[1]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_accept_greedy(B, V, total_nodes, max_nodes_per_req, _ptr(node_offsets), _ptr(parent),
+                                  _ptr(draft_tokens), _ptr(target_logits), _dtype_code(target_logits),
+                                  _ptr(accept_len), _ptr(out_tokens), out_tokens.shape[1], _ptr(stop_node),
+                                  _ptr(row_argmax), _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_accept_greedy", rc)

@@ -121,6 +121,7 @@ int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
     return SPEC_ERR_UNSUPPORTED;
   if (q_kind != SPEC_Q_LOGITS && q_kind != SPEC_Q_PROBS) return SPEC_ERR_UNSUPPORTED;
   if (total_nodes > 0 && n_q_rows == 0) return SPEC_ERR_SHAPE;
+  if (static_cast<int64_t>(total_nodes) + B + n_q_rows > 65535) return SPEC_ERR_UNSUPPORTED;   // rows are the statistics grid's y dimension
   if (B == 0) return SPEC_OK;
   if (!node_offsets || !target_logits || !u_resample || !accept_len || !out_tokens) return SPEC_ERR_NULL;
   if (total_nodes > 0 && (!draft_tokens || !draft_q || !q_row || !u_accept)) return SPEC_ERR_NULL;
@@ -133,6 +134,35 @@ int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
   a.u_accept = u_accept; a.u_resample = u_resample; a.accept_len = accept_len; a.out_tokens = out_tokens;
   a.out_stride = out_stride; a.stop_node = stop_node; a.dbg_ratio = dbg_ratio; a.workspace = workspace;
   launch_accept(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
+size_t spec_accept_greedy_workspace_size(int32_t B, int32_t total_nodes, int32_t V) {
+  if (B < 0 || total_nodes < 0 || V <= 0) return 0;
+  return greedy_workspace_bytes(B, total_nodes, V);
+}
+
+int32_t spec_accept_greedy(int32_t B, int32_t V, int32_t total_nodes, int32_t max_nodes_per_req,
+                           const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+                           const void* target_logits, int32_t target_dtype, int32_t* accept_len,
+                           int32_t* out_tokens, int32_t out_stride, int32_t* stop_node, int32_t* row_argmax,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (B < 0 || V <= 0 || total_nodes < 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
+  if (max_nodes_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (out_stride < max_nodes_per_req + 1) return SPEC_ERR_SHAPE;
+  if (target_dtype != SPEC_BF16 && target_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(total_nodes) + B > 65535) return SPEC_ERR_UNSUPPORTED;   // rows are the grid's y dimension
+  if (B == 0) return SPEC_OK;
+  if (!node_offsets || !target_logits || !accept_len || !out_tokens) return SPEC_ERR_NULL;
+  if (total_nodes > 0 && !draft_tokens) return SPEC_ERR_NULL;
+  const size_t need = greedy_workspace_bytes(B, total_nodes, V);
+  if (!workspace || workspace_bytes < need) return SPEC_ERR_WORKSPACE;
+  GreedyArgs a{};
+  a.B = B; a.V = V; a.total_nodes = total_nodes; a.node_offsets = node_offsets; a.parent = parent;
+  a.draft_tokens = draft_tokens; a.target = target_logits; a.t_dtype = target_dtype; a.accept_len = accept_len;
+  a.out_tokens = out_tokens; a.out_stride = out_stride; a.stop_node = stop_node; a.row_argmax = row_argmax;
+  a.workspace = workspace;
+  launch_accept_greedy(a, static_cast<hipStream_t>(stream));
   return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
 }
 

@@ -34,6 +34,22 @@ struct AcceptArgs {
 size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V);
 void launch_accept(const AcceptArgs& a, hipStream_t stream);
 
+// ---- greedy.hip -------------------------------------------------------------------
+struct GreedyArgs {
+  int B, V, total_nodes;
+  const int32_t* node_offsets;
+  const int32_t* parent;
+  const int32_t* draft_tokens;
+  const void* target; int t_dtype;
+  int32_t* accept_len;
+  int32_t* out_tokens; int out_stride;
+  int32_t* stop_node;
+  int32_t* row_argmax;
+  void* workspace;
+};
+size_t greedy_workspace_bytes(int B, int total_nodes, int V);
+void launch_accept_greedy(const GreedyArgs& a, hipStream_t stream);
+
 // ---- fuse.hip ---------------------------------------------------------------------
 struct FuseArgs {
   int B, k_max, N, V;

@@ -121,3 +121,38 @@ class DeviceAccept:
         return dict(accept_len=self.accept_len.cpu().numpy(), out_tokens=self.out_tokens.cpu().numpy(),
                     stop_node=self.stop_node.cpu().numpy(),
                     ratio=None if self.dbg_ratio is None else self.dbg_ratio.cpu().numpy()[:self.total])
+
+
+class DeviceGreedy:
+    """Device copies of the greedy-verification inputs of one batch, its outputs and workspace."""
+
+    def __init__(self, st: W.DraftStructure, target_logits, draft_tokens, device="cuda"):
+        self.B = int(st.n.shape[0])
+        self.total = st.total
+        self.max_nodes = int(st.n.max()) if self.B else 0
+        self.node_offsets = _i32(st.node_offsets, device)
+        self.parent = None if st.parent is None else _i32(st.parent, device)
+        if isinstance(target_logits, torch.Tensor):
+            self.target = target_logits
+        elif target_logits.dtype == np.uint16:
+            self.target = bf16_to_device(target_logits, device)
+        else:
+            self.target = torch.from_numpy(np.ascontiguousarray(target_logits)).to(device)
+        self.draft_tokens = draft_tokens if isinstance(draft_tokens, torch.Tensor) else _i32(draft_tokens, device)
+        self.accept_len = torch.zeros(self.B, dtype=torch.int32, device=device)
+        self.out_tokens = torch.zeros((self.B, self.max_nodes + 1), dtype=torch.int32, device=device)
+        self.stop_node = torch.zeros(self.B, dtype=torch.int32, device=device)
+        self.row_argmax = torch.zeros(self.total + self.B, dtype=torch.int32, device=device)
+        self.V = self.target.shape[1]
+        ws = sv.spec_accept_greedy_workspace_size(self.B, self.total, self.V)
+        self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=device)
+
+    def run(self, stream=None):
+        sv.spec_accept_greedy(self.B, self.total, self.max_nodes, self.node_offsets, self.parent, self.draft_tokens,
+                              self.target, self.accept_len, self.out_tokens, self.stop_node, self.row_argmax,
+                              self.workspace, stream)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return dict(accept_len=self.accept_len.cpu().numpy(), out_tokens=self.out_tokens.cpu().numpy(),
+                    stop_node=self.stop_node.cpu().numpy(), row_argmax=self.row_argmax.cpu().numpy())
