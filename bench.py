@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching every call from the host")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
+    ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
+                    help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
+                         "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
     return ap.parse_args()
 
 
@@ -54,7 +57,7 @@ def read_traffic(workload):
 class Step:
     """Device state of one input copy and the three calls of one step."""
 
-    def __init__(self, cfg, a, ai, runner, sv):
+    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling"):
         import torch
         self.attn = runner.DeviceAttn(a, want_lse=False)
         st = a.st
@@ -88,13 +91,17 @@ class Step:
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
                                               want_debug=False)
 
+        if accept_mode == "greedy":
+            # same target rows and draft tokens, no draft distributions or uniforms
+            self.accept = runner.DeviceGreedy(st, self.accept.target, self.accept.draft_tokens)
+
     def run(self):
         self.attn.run()
         self.fuse.run()
         self.accept.run()
 
 
-def cpu_baseline(cfg, a, ai, budget_s):
+def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling"):
     """The oracle, as it stands, timed on the host cores over whole batches of the workload."""
     import oracle
     reps, t_total = 0, 0.0
@@ -108,8 +115,11 @@ def cpu_baseline(cfg, a, ai, budget_s):
             toks, qrow, dq = rf["fused_token"].reshape(-1), rf["q_row"].reshape(-1), ai.fusion.draft_logits
         else:
             toks, qrow, dq = ai.draft_tokens, ai.q_row, ai.draft_q
-        oracle.accept(a.st.node_offsets, a.st.parent, toks, ai.target_logits, dq, qrow, ai.u_accept,
-                      ai.u_resample, temperature=cfg.temperature)
+        if accept_mode == "greedy":
+            oracle.accept_greedy(a.st.node_offsets, a.st.parent, toks, ai.target_logits)
+        else:
+            oracle.accept(a.st.node_offsets, a.st.parent, toks, ai.target_logits, dq, qrow, ai.u_accept,
+                          ai.u_resample, temperature=cfg.temperature)
         t_total += time.perf_counter() - t0
         reps += 1
     return dict(value=tokens * reps / t_total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
@@ -133,7 +143,7 @@ def main():
     cfg = W.CONFIGS[args.workload]
     a = W.make_attn_inputs(cfg, seed=args.seed)
     ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
-    copies = [Step(cfg, a, ai, runner, sv) for _ in range(max(1, args.copies))]
+    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode) for _ in range(max(1, args.copies))]
     torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -192,7 +202,14 @@ def main():
     tokens = int(a.st.total)
     attn_bytes, attn_flops = W.attention_bytes_flops(cfg, a.st)
     n_logit_rows = ai.target_logits.shape[0] + (ai.fusion.draft_logits.shape[0] if ai.fusion else ai.draft_q.shape[0])
+    if args.accept_mode == "greedy":
+        n_logit_rows = ai.target_logits.shape[0]          # no draft distributions are read
     accept_bytes = n_logit_rows * cfg.vocab * 2
+    # the attention kernel the library's plan picks for this shape (all query rows that share a KV head)
+    max_rows = int(a.st.n.max()) * (cfg.n_q_heads // cfg.n_kv_heads)
+    attn_kernel = (f"attn_stream_kernel<{cfg.head_dim}> (token-split, one workgroup per request x KV head x context chunk)"
+                   if max_rows <= 128 else
+                   f"attn_rows_kernel<{cfg.head_dim},8> (row-split, 8 waves share each K/V tile)")
     achieved = attn_bytes / attn_s / 1e9
     out = {
         "metric": METRIC,
@@ -208,12 +225,13 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "launch_mode": "eager" if graphs is None else "hip_graph_replay",
+        "accept_mode": args.accept_mode,
         "config": {"workload": cfg.name, "batch": cfg.batch, "draft_tokens_per_step": tokens,
                    "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
                    "context": str(cfg.ctx), "draft": str(cfg.draft), "vocab": cfg.vocab,
                    "input_copies_rotated": len(copies)},
         "step_hbm_gbs": (attn_bytes + accept_bytes) / (elapsed / args.steps) / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn: attn_stream_kernel<128,1> (one workgroup per request x KV head, no context split on this workload)",
+        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn: " + attn_kernel + "; duration is the whole call, incl. the chunk-combine kernel where the context is split",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": read_traffic(cfg.name), "algorithmic_bytes": attn_bytes,
                      "launch_us_mean": attn_s * 1e6, "launch_us_p10": float(np.percentile(attn_ms, 10)) * 1e3,
@@ -221,7 +239,7 @@ def main():
                      "mfma_tflops": attn_flops / attn_s / 1e12},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds, args.accept_mode)
     print(json.dumps(out))
 
 
