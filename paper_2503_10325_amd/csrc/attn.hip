@@ -59,6 +59,7 @@ struct AttnParams {
   float* ws_o;       // [rows, max_chunks, D] unnormalised partial outputs
   float2* ws_ml;     // [rows, max_chunks] (max in log2 units, sum)
   int B, Hq, Hkv, G, max_pages, chunk_tokens, max_chunks;
+  int tau;           // > 0: a request is cut so that one wave streams at most tau tiles per work item
   float c;           // scale * log2(e)
   int out_f32;
 };
@@ -81,6 +82,25 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// The value held by the same lane of the other half-wave (lane ^ 32), through the gfx950 half-wave
+// swap instead of an LDS round trip: after swapping the upper half of one copy with the lower half
+// of another, lane l of the first copy holds x[l % 32] and of the second x[32 + l % 32].
+__device__ __forceinline__ void half_pair(float x, float& lo_half, float& hi_half) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  lo_half = __uint_as_float(r[0]);
+  hi_half = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float half_max(float x) {
+  float a, b;
+  half_pair(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float half_sum(float x) {
+  float a, b;
+  half_pair(x, a, b);
+  return a + b;
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ u32x4 zero4() {
@@ -95,20 +115,37 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, x);
 }
 
+// Waves of a token-split workgroup that share one query block, for R <= 128 query rows.
+__device__ __forceinline__ int stream_nslice(int R) {
+  const int nqb = min(4, (R + 31) / 32);
+  return nqb <= 1 ? 4 : (nqb <= 2 ? 2 : 1);
+}
+
+// Number of context chunks of a request with L tokens and n draft nodes.  The token-split,
+// sorted-work-list launch (tau > 0) cuts by the number of tiles one wave streams; the other
+// launches cut by tokens.  The attention kernels and the combine kernel all use this function.
+__device__ __forceinline__ int request_chunks(const AttnParams& P, int L, int n) {
+  if (P.tau > 0) {
+    const int nslice = stream_nslice(min(n * P.G, 128));
+    const int per_wave = ((L + kTile - 1) / kTile + nslice - 1) / nslice;
+    return min(max(1, (per_wave + P.tau - 1) / P.tau), P.max_chunks);
+  }
+  return max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+}
+
 // Token-split kernel (up to 128 query rows per KV head and workgroup).  The 4 waves of a
 // workgroup take roles from the number of 32-row query blocks nqb of the request:
 //   nqb = 1: the four waves stream every 4th tile for the same query block;
 //   nqb = 2: two waves per query block, each streaming every 2nd tile;
 //   nqb = 3, 4: one wave per query block, streaming every tile.
 // Waves that share tokens fetch them separately (the repeats hit in L2: HBM traffic stays 1x).
+// One work item: (request b, KV head kvh, context chunk, row group rg).  Every return below is
+// workgroup-uniform.
 template <int D>
-__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams P) {
+__device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg) {
   using C = AttnCfg<D>;
-  extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int b = blockIdx.z, kvh = blockIdx.y;
-  const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
 
   const int q0 = P.q_offsets[b];
   int n = P.q_offsets[b + 1] - q0;
@@ -124,7 +161,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
   const int nslice = kAttnWaves / nqbp;                     // waves sharing one query block
   const int my_qb = wave % nqbp, my_slice = wave / nqbp;
   const bool wave_active = my_qb < nqb;                     // wave-uniform
-  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+  const int nchunks = request_chunks(P, L, n);
   if (chunk >= nchunks) return;
   const int cb = (((L + nchunks - 1) / nchunks) + kTile - 1) & ~(kTile - 1);
   const int t_begin = chunk * cb;
@@ -251,7 +288,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
   };
 
   const long long prof_t0 = PROF_T();
-  long long prof_store = 0, prof_compute = 0, prof_tiles = 0;
+  long long prof_store = 0, prof_compute = 0, prof_tiles = 0, prof_qk = 0, prof_sm = 0;
   int t = my_slice;
   if (wave_active && t < ntiles) {
     fetch_pages(t);
@@ -310,6 +347,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
     }
 
+    const long long prof_q = PROF_T();
     // ---- mask, online softmax ----
     const bool need_mask = tok0 + kTile > ctx;
     float tmax = -INFINITY;
@@ -326,7 +364,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
       tmax = fmaxf(tmax, v);
     }
     tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    tmax = half_max(tmax);
     const float m_new = fmaxf(m_run, tmax);
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = fast_exp2(m_run - m_safe);
@@ -336,6 +374,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
+    const long long prof_s = PROF_T();
     // ---- P^T as two bf16 terms (value + rounding residual), 16 tokens at a time; O^T += V^T P^T ----
     // A single bf16 rounding of P (2^-9 relative) would dominate the output error; carrying the
     // rounding residual in a second bf16 term keeps ~16 bits of every weight.
@@ -368,12 +407,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
     const long long prof_c = PROF_T();
     prof_store += prof_b - prof_a;
     prof_compute += prof_c - prof_b;
+    prof_qk += prof_q - prof_b;
+    prof_sm += prof_s - prof_q;
     prof_tiles += 1;
   }
   const long long prof_t1 = PROF_T();
 
   // ---- merge the waves that share a query block ----
-  l_run += __shfl_xor(l_run, 32, kWave);
+  l_run = half_sum(l_run);
   __syncthreads();                         // every wave is done with its tile memory
   if (lane < 32) {
     sh_m[wave * 32 + lane] = m_run;
@@ -449,7 +490,74 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
   PROF_ADD(3, prof_compute);
   PROF_ADD(4, prof_tiles);
   PROF_ADD(5, PROF_T() - prof_t1);
+  PROF_ADD(6, prof_qk);
+  PROF_ADD(7, prof_sm);
   (void)prof_t0; (void)prof_t1; (void)prof_store; (void)prof_compute; (void)prof_tiles;
+}
+
+// Grid-mapped launch: blockIdx = (chunk + max_chunks * row group, KV head, request); workgroups
+// whose chunk does not exist return at once.
+template <int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams P) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  stream_item<D>(P, smem, blockIdx.z, blockIdx.y, blockIdx.x % P.max_chunks, blockIdx.x / P.max_chunks);
+}
+
+// Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
+// is two workgroups per compute unit; every workgroup derives the same list of work items
+// (request, chunk, KV head) from the lengths on the device, ordered by decreasing number of tiles
+// a wave streams per item, and takes items blockIdx.x, blockIdx.x + gridDim.x, ...: long items
+// start first, short ones fill the tail, and no workgroup is launched for chunks that do not exist.
+constexpr int kPlanMaxB = 128;
+
+template <int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnParams P) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int sh_first[kPlanMaxB + 1];        // first item of the request at sorted position s
+  __shared__ unsigned char sh_order[kPlanMaxB];  // request at sorted position s
+  const int tid = threadIdx.x;
+  int* key = reinterpret_cast<int*>(smem);       // scratch in the tile memory, dead before the first item
+  int* cnt = key + kPlanMaxB;
+  int my_key = -1, my_cnt = 0;
+  if (tid < P.B) {
+    int n = P.q_offsets[tid + 1] - P.q_offsets[tid];
+    n = n > kMaxQ ? kMaxQ : n;
+    if (n > 0) {
+      const int L = P.ctx_len[tid] + n;
+      const int nch = request_chunks(P, L, n);
+      const int nslice = stream_nslice(min(n * P.G, 128));
+      const int per_wave = ((L + kTile - 1) / kTile + nslice - 1) / nslice;
+      my_key = (per_wave + nch - 1) / nch;       // tiles one wave streams per item of this request
+      my_cnt = nch * P.Hkv;
+    }
+  }
+  if (tid < kPlanMaxB) { key[tid] = my_key; cnt[tid] = my_cnt; }
+  __syncthreads();
+  if (tid < P.B) {
+    int rank = 0, first = 0;
+    for (int j = 0; j < P.B; ++j) {
+      const int kj = key[j];
+      const bool before = kj > my_key || (kj == my_key && j < tid);
+      rank += before ? 1 : 0;
+      first += before ? cnt[j] : 0;
+    }
+    sh_order[rank] = static_cast<unsigned char>(tid);
+    sh_first[rank] = first;
+    if (rank == P.B - 1) sh_first[P.B] = first + my_cnt;
+  }
+  __syncthreads();
+  const int total = sh_first[P.B];
+  for (int item = blockIdx.x; item < total; item += gridDim.x) {
+    int lo = 0, hi = P.B;                         // largest s with sh_first[s] <= item
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (sh_first[mid] <= item) lo = mid; else hi = mid;
+    }
+    const int b = sh_order[lo];
+    const int local = item - sh_first[lo];
+    stream_item<D>(P, smem, b, local % P.Hkv, local / P.Hkv, 0);
+    __syncthreads();                              // the tile memory is reused by the next item
+  }
 }
 
 // ----------------------------------------------------------------------------------
@@ -695,7 +803,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
 #pragma unroll
       for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[tb][r]);
     tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    tmax = half_max(tmax);
     const float m_new = fmaxf(m_run, tmax);
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = fast_exp2(m_run - m_safe);
@@ -776,7 +884,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
 
   // ---- write this wave's rows ----
   if (!active) return;
-  l_run += __shfl_xor(l_run, 32, kWave);
+  l_run = half_sum(l_run);
   if (!valid) return;
   if (nchunks == 1) {
     const float inv = 1.f / l_run;
@@ -830,7 +938,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P, int tot
   n = n > kMaxQ ? kMaxQ : n;
   if (qi - P.q_offsets[b] >= n) return;
   const int L = P.ctx_len[b] + n;
-  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+  const int nchunks = request_chunks(P, L, n);
   if (nchunks == 1) return;
   float M = -INFINITY;
   for (int c = 0; c < nchunks; ++c) M = fmaxf(M, P.ws_ml[grow * P.max_chunks + c].x);
@@ -869,10 +977,14 @@ struct AttnPlan {
   int row_groups;
   int chunk_tokens;
   int max_chunks;
+  int tau;            // > 0: sorted-work-list launch of the token-split kernel, at most tau tiles per wave and item
 };
+
+constexpr int kListMaxChunks = 16;
 
 static AttnPlan make_plan(const AttnArgs& a) {
   AttnPlan p;
+  p.tau = 0;
   const int G = a.Hq / a.Hkv;
   const int max_rows = a.max_q * G;
   if (max_rows <= 128) { p.kind = 0; p.rows_per_wg = 128; }
@@ -913,6 +1025,24 @@ static AttnPlan make_plan(const AttnArgs& a) {
   p.chunk_tokens = static_cast<int>(chunk);
   p.max_chunks = static_cast<int>((max_tok + chunk - 1) / chunk);
   if (p.max_chunks < 1) p.max_chunks = 1;
+  // Small batches whose lengths are ragged run the token-split kernel from a sorted work list built
+  // on the device (the lengths are device data); there chunks are cut by tiles per wave, not by
+  // tokens.  The list costs every workgroup one extra round of dependent loads (~5 us per launch),
+  // which only pays when lengths differ: the caller's total-token hint against batch x longest
+  // request says whether they do.
+  const bool ragged = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok;
+  int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 32 : 0;
+  if (const char* e = getenv("SPECV_ATTN_TAU")) {         // development knob for sweeps (0: grid-mapped launch)
+    const int v = atoi(e);
+    if (token_split && a.B <= kPlanMaxB && v >= 0 && v <= 255) tau = v;
+  }
+  if (getenv("SPECV_ATTN_JOBS")) tau = 0;
+  if (tau > 0) {
+    const int64_t max_tiles = (max_tok + kTile - 1) / kTile;     // tiles of the longest request when one wave streams them all
+    const int64_t mc = (max_tiles + tau - 1) / tau;
+    p.tau = tau;
+    p.max_chunks = static_cast<int>(mc < 1 ? 1 : (mc > kListMaxChunks ? kListMaxChunks : mc));
+  }
   return p;
 }
 
@@ -942,6 +1072,19 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
   static_assert(kMerge <= kTiles, "merge buffers must fit in the tile memory");
   static bool attr_done = false;
   if (set_lds_once(&attn_stream_kernel<D>, kTiles, attr_done) != 0) return -6;
+  if (plan.tau > 0) {
+    static bool list_attr_done = false;
+    if (set_lds_once(&attn_stream_list_kernel<D>, kTiles, list_attr_done) != 0) return -6;
+    static int n_cu = 0;
+    if (n_cu == 0) {
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+        n_cu = 256;
+    }
+    hipLaunchKernelGGL((attn_stream_list_kernel<D>), dim3(2 * n_cu), dim3(kAttnThreads), kTiles, stream, P);
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+  }
   dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
   hipLaunchKernelGGL((attn_stream_kernel<D>), grid, dim3(kAttnThreads), kTiles, stream, P);
   return hipGetLastError() == hipSuccess ? 0 : -6;
@@ -971,7 +1114,7 @@ int launch_attn(const AttnArgs& a, hipStream_t stream) {
   P.ws_o = reinterpret_cast<float*>(static_cast<unsigned char*>(a.workspace) +
                                     ((rows * plan.max_chunks * sizeof(float2) + 255) / 256) * 256);
   P.B = a.B; P.Hq = a.Hq; P.Hkv = a.Hkv; P.G = a.Hq / a.Hkv; P.max_pages = a.max_pages;
-  P.chunk_tokens = plan.chunk_tokens; P.max_chunks = plan.max_chunks;
+  P.chunk_tokens = plan.chunk_tokens; P.max_chunks = plan.max_chunks; P.tau = plan.tau;
   P.c = a.scale * kLog2e;
   P.out_f32 = (a.out_dtype == kF32);
   int rc;

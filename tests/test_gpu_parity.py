@@ -55,6 +55,26 @@ def test_attention_matches_oracle(rt, name):
     assert np.abs(lse - ref_lse).max() < 2e-2, f"{name}: lse err {np.abs(lse - ref_lse).max()}"
 
 
+@pytest.mark.parametrize("name", ["ragged_gqa8", "d64_gqa2", "linear_multi_chunk", "tree_small_gqa"])
+@pytest.mark.parametrize("hint", ["none", "exact", "small"])
+def test_attention_launch_modes(rt, name, hint):
+    """The total-token hint only steers how the work is cut (grid-mapped chunks when it is absent or
+    says the lengths are uniform, a sorted work list when it says they are ragged): results must
+    meet the same bar whatever it says, including a hint far below the truth."""
+    cfg = ATTN_CASES[name]
+    a = W.make_attn_inputs(cfg, seed=12)
+    ref, ref_lse = oracle_attn(a)
+    true_total = int((a.st.ctx_len.astype(np.int64) + a.st.n).sum())
+    kv_hint = {"none": 0, "exact": true_total, "small": max(1, true_total // 7)}[hint]
+    dev = rt.DeviceAttn(a, kv_hint=kv_hint)
+    dev.run()
+    torch.cuda.synchronize()
+    got = dev.out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    assert attn_rel_err(got, ref) <= ATTN_TOL
+    assert np.abs(dev.lse.cpu().numpy() - ref_lse).max() < 2e-2
+
+
 def test_attention_fp32_output_and_determinism(rt):
     cfg = ATTN_CASES["ragged_gqa8"]
     a = W.make_attn_inputs(cfg, seed=5)
