@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching every call from the host")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
+    ap.add_argument("--fuse", choices=["auto", "always"], default="auto",
+                    help="auto: spec_fuse_drafts runs on workloads with several drafters (its only use in the method); "
+                         "always: single-drafter workloads also run it with N = 1 (an identity)")
     ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
                     help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
                          "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
@@ -57,7 +60,7 @@ def read_traffic(workload):
 class Step:
     """Device state of one input copy and the three calls of one step."""
 
-    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling"):
+    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto"):
         import torch
         self.attn = runner.DeviceAttn(a, want_lse=False)
         st = a.st
@@ -69,35 +72,39 @@ class Step:
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
                                               want_debug=False)
         else:
-            # single drafter: the fusion step degenerates to N = 1 (identity) but still runs
+            # single drafter: token fusion has nothing to fuse.  With --fuse always it still runs with
+            # N = 1 (an identity) and, for linear drafts of uniform length, feeds the acceptance step.
             B, k_max = cfg.batch, int(st.n.max())
-            from paper_2503_10325_amd import workloads as W
-            conf = np.ones((B, k_max, 1), dtype=np.float32)
-            toks = np.zeros((B, k_max, 1), dtype=np.int32)
-            for b in range(B):
-                o, k = int(st.node_offsets[b]), int(st.n[b])
-                toks[b, :k, 0] = ai.draft_tokens[o:o + k]
-            f = W.FusionInputs(1, k_max, st.n.astype(np.int32), conf, toks, None)
-            self.fuse = runner.DeviceFuse(f, cfg.vocab, temperature=cfg.temperature,
-                                          draft_logits_dev=torch.empty(0, device="cuda"))
-            self.fuse.draft_logits = None
-            # Only for linear drafts of uniform length are the fused [B, k] outputs the flat node
-            # arrays (node j's draft row is row j).  Tree nodes index their parent's draft row, so
-            # tree and ragged workloads keep the generator's q_row / tokens.
-            uniform = st.parent is None and int(st.n.min()) == int(st.n.max())
+            self.fuse = None
+            uniform = False
+            if fuse == "always":
+                from paper_2503_10325_amd import workloads as W
+                conf = np.ones((B, k_max, 1), dtype=np.float32)
+                toks = np.zeros((B, k_max, 1), dtype=np.int32)
+                for b in range(B):
+                    o, k = int(st.node_offsets[b]), int(st.n[b])
+                    toks[b, :k, 0] = ai.draft_tokens[o:o + k]
+                f = W.FusionInputs(1, k_max, st.n.astype(np.int32), conf, toks, None)
+                self.fuse = runner.DeviceFuse(f, cfg.vocab, temperature=cfg.temperature,
+                                              draft_logits_dev=torch.empty(0, device="cuda"))
+                self.fuse.draft_logits = None
+                # Only for linear drafts of uniform length are the fused [B, k] outputs the flat node
+                # arrays (node j's draft row is row j).  Tree nodes index their parent's draft row, so
+                # tree and ragged workloads keep the generator's q_row / tokens.
+                uniform = st.parent is None and int(st.n.min()) == int(st.n.max())
             self.accept = runner.DeviceAccept(st, ai.target_logits, ai.draft_q,
                                               self.fuse.q_row.view(-1) if uniform else ai.q_row,
                                               self.fuse.fused_token.view(-1) if uniform else ai.draft_tokens,
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
                                               want_debug=False)
-
         if accept_mode == "greedy":
             # same target rows and draft tokens, no draft distributions or uniforms
             self.accept = runner.DeviceGreedy(st, self.accept.target, self.accept.draft_tokens)
 
     def run(self):
         self.attn.run()
-        self.fuse.run()
+        if self.fuse is not None:
+            self.fuse.run()
         self.accept.run()
 
 
@@ -143,7 +150,7 @@ def main():
     cfg = W.CONFIGS[args.workload]
     a = W.make_attn_inputs(cfg, seed=args.seed)
     ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
-    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode) for _ in range(max(1, args.copies))]
+    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse) for _ in range(max(1, args.copies))]
     torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -226,6 +233,8 @@ def main():
         "data": "synthetic",
         "launch_mode": "eager" if graphs is None else "hip_graph_replay",
         "accept_mode": args.accept_mode,
+        "calls_per_step": ["spec_verify_attn"] + (["spec_fuse_drafts"] if copies[0].fuse is not None else []) +
+                          ["spec_accept" if args.accept_mode == "sampling" else "spec_accept_greedy"],
         "config": {"workload": cfg.name, "batch": cfg.batch, "draft_tokens_per_step": tokens,
                    "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
                    "context": str(cfg.ctx), "draft": str(cfg.draft), "vocab": cfg.vocab,
