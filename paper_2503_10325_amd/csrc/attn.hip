@@ -921,22 +921,17 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
 
 // Merge the per-chunk partials of every (query row, head) that spans several chunks.
 template <int D>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P, int total_rows) {
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P) {
   constexpr int kPer = D / 32;
-  const int64_t grow = static_cast<int64_t>(blockIdx.x) * 8 + (threadIdx.x >> 5);
-  if (grow >= total_rows) return;
-  const int d0 = (threadIdx.x & 31) * kPer;
-  const int qi = static_cast<int>(grow / P.Hq);
-  // request that owns query row qi (q_offsets is sorted)
-  int lo = 0, hi = P.B;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (P.q_offsets[mid] <= qi) lo = mid; else hi = mid;
-  }
-  const int b = lo;
-  int n = P.q_offsets[b + 1] - P.q_offsets[b];
+  // blockIdx.y = request; 8 (query node, head) rows of it per workgroup, 32 threads per row
+  const int b = blockIdx.y;
+  const int q0 = P.q_offsets[b];
+  int n = P.q_offsets[b + 1] - q0;
   n = n > kMaxQ ? kMaxQ : n;
-  if (qi - P.q_offsets[b] >= n) return;
+  const int local = blockIdx.x * 8 + (threadIdx.x >> 5);
+  if (local >= n * P.Hq) return;
+  const int64_t grow = static_cast<int64_t>(q0) * P.Hq + local;
+  const int d0 = (threadIdx.x & 31) * kPer;
   const int L = P.ctx_len[b] + n;
   const int nchunks = request_chunks(P, L, n);
   if (nchunks == 1) return;
@@ -1123,10 +1118,10 @@ int launch_attn(const AttnArgs& a, hipStream_t stream) {
   else rc = launch_rows<128, 8>(P, plan, a.B, a.Hkv, stream);
   if (rc != 0) return rc;
   if (plan.max_chunks > 1) {
-    const int total_rows = static_cast<int>(rows);
-    dim3 grid((total_rows + 7) / 8);
-    if (a.D == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, grid, dim3(256), 0, stream, P, total_rows);
-    else hipLaunchKernelGGL(attn_combine_kernel<64>, grid, dim3(256), 0, stream, P, total_rows);
+    const int max_q = a.max_q > kMaxQ ? kMaxQ : a.max_q;
+    dim3 grid((max_q * a.Hq + 7) / 8, a.B);
+    if (a.D == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, grid, dim3(256), 0, stream, P);
+    else hipLaunchKernelGGL(attn_combine_kernel<64>, grid, dim3(256), 0, stream, P);
     if (hipGetLastError() != hipSuccess) return -6;
   }
   return 0;
