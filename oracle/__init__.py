@@ -186,3 +186,24 @@ def accept_greedy(node_offsets, parent, draft_tokens, target_logits, out_stride=
     if rc != 0:
         raise RuntimeError(f"oracle_accept_greedy failed: {rc}")
     return dict(accept_len=accept_len, out_tokens=out_tokens, stop_node=stop, row_argmax=arg)
+
+
+def routing_scores(k_len, conf, draft_tokens, accept_len, out_tokens, embedding):
+    """Routing-score update (Eq. 1-2).  conf, draft_tokens [B, k_max, N]; out_tokens [B, stride];
+    embedding [V, E] (bf16 bits or fp32).  Returns scores [B, N] fp64."""
+    conf = np.ascontiguousarray(conf, dtype=np.float32)
+    B, k_max, N = conf.shape
+    draft_tokens = _i32(draft_tokens).reshape(B, k_max, N)
+    k_len, accept_len = _i32(k_len), _i32(accept_len)
+    out_tokens = _i32(out_tokens)
+    emb, edt = _logits(embedding)
+    V, E = emb.shape
+    assert out_tokens.shape[0] == B
+    scores = np.zeros((B, N), dtype=np.float64)
+    rc = lib().oracle_routing_scores(
+        ctypes.c_int(B), ctypes.c_int(k_max), ctypes.c_int(N), ctypes.c_int(V), ctypes.c_int(E), _p(k_len),
+        _p(conf), _p(draft_tokens), _p(accept_len), _p(out_tokens), ctypes.c_int(out_tokens.shape[1]), _p(emb),
+        ctypes.c_int(edt), _p(scores))
+    if rc != 0:
+        raise RuntimeError(f"oracle_routing_scores failed: {rc}")
+    return scores

@@ -28,6 +28,11 @@
  *                         a draft token is kept when it is the target's most likely
  *                         token at its position; the first mismatch is replaced by
  *                         that most likely token.
+ *   oracle_routing_scores - the routing-score update that follows acceptance
+ *                         (Section 4.1, Eq. 1 and Eq. 2): per drafter, the mean over
+ *                         draft positions of the normalised harmonic combination of
+ *                         its confidence and the cosine similarity between its token's
+ *                         embedding and the accepted token's embedding.
  *
  * Pins: tests/test_oracle_*.py (closed forms, chi-square, brute force on tiny
  * vocabularies, library SDPA on the causal special case, tree/path equivalence).
@@ -381,6 +386,51 @@ int oracle_accept_greedy(int B, int V, const int32_t* node_offsets, const int32_
     }
     accept_len[b] = depth;
     if (stop_node) stop_node[b] = cur;
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* routing scores                                                              */
+/* ------------------------------------------------------------------------- */
+/*
+ * Eq. 1: d[b,i,n] = cos(H(accepted token i of request b), H(draft_tokens[b,i,n])) for
+ * positions i < accept_len[b] (0-based: the positions whose draft was accepted), 0
+ * otherwise.  Eq. 2: scores[b,n] = (1/K) sum_i c d / (c d + (1-c)(1-d)), K = k_len[b].
+ * Readings where the paper is silent: a negative cosine counts as 0 (Eq. 2 takes values in
+ * (0,1)); a zero embedding row gives cosine 0; a term whose denominator is not positive
+ * (c = 1, d = 0 or c = 0, d = 1) is 0; K = 0 gives score 0.
+ * conf, draft_tokens: [B, k_max, N]; out_tokens: [B, out_stride]; embedding: [V, E].
+ */
+int oracle_routing_scores(int B, int k_max, int N, int V, int E, const int32_t* k_len, const float* conf,
+                          const int32_t* draft_tokens, const int32_t* accept_len, const int32_t* out_tokens,
+                          int out_stride, const void* embedding, int edt, double* scores) {
+  (void)V;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    const int K = k_len[b];
+    for (int n = 0; n < N; ++n) {
+      double sum = 0.0;
+      for (int i = 0; i < K && i < k_max; ++i) {
+        double d = 0.0;
+        if (i < accept_len[b]) {
+          const int64_t ra = (int64_t)out_tokens[(int64_t)b * out_stride + i] * E;
+          const int64_t rx = (int64_t)draft_tokens[((int64_t)b * k_max + i) * N + n] * E;
+          double dot = 0.0, na = 0.0, nx = 0.0;
+          for (int e = 0; e < E; ++e) {
+            const double a = load_logit(embedding, edt, ra + e), x = load_logit(embedding, edt, rx + e);
+            dot += a * x; na += a * a; nx += x * x;
+          }
+          if (na > 0.0 && nx > 0.0) d = dot / (sqrt(na) * sqrt(nx));
+          if (d < 0.0) d = 0.0;
+          if (d > 1.0) d = 1.0;                 /* rounding of identical rows */
+        }
+        const double c = (double)conf[((int64_t)b * k_max + i) * N + n];
+        const double den = c * d + (1.0 - c) * (1.0 - d);
+        if (den > 0.0) sum += c * d / den;
+      }
+      scores[(int64_t)b * N + n] = (K > 0) ? sum / (double)K : 0.0;
+    }
   }
   return 0;
 }
