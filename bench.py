@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--fuse", choices=["auto", "always"], default="auto",
                     help="auto: spec_fuse_drafts runs on workloads with several drafters (its only use in the method); "
                          "always: single-drafter workloads also run it with N = 1 (an identity)")
+    ap.add_argument("--routing", action="store_true",
+                    help="multi-drafter workloads: also run spec_routing_scores (Eq. 1-2) after acceptance, on a "
+                         "synthetic [vocab, 4096] bf16 embedding table")
     ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
                     help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
                          "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
@@ -60,8 +63,9 @@ def read_traffic(workload):
 class Step:
     """Device state of one input copy and the three calls of one step."""
 
-    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto"):
+    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto", routing=False):
         import torch
+        self.routing = None
         self.attn = runner.DeviceAttn(a, want_lse=False)
         st = a.st
         if ai.fusion is not None:
@@ -97,6 +101,14 @@ class Step:
                                               self.fuse.fused_token.view(-1) if uniform else ai.draft_tokens,
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
                                               want_debug=False)
+        if routing and ai.fusion is not None and accept_mode == "sampling":
+            from paper_2503_10325_amd import workloads as W
+            f = ai.fusion
+            emb = runner.bf16_to_device(W._normal_bf16(W._rng(0, cfg.name, "embedding"), (cfg.vocab, 4096)), "cuda")
+            t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
+            scores = torch.zeros((cfg.batch, f.n_drafters), dtype=torch.float32, device="cuda")
+            args = (t(f.k_len), t(f.conf), t(f.draft_tokens), self.accept.accept_len, self.accept.out_tokens, emb, scores)
+            self.routing = lambda: sv.spec_routing_scores(*args)
         if accept_mode == "greedy":
             # same target rows and draft tokens, no draft distributions or uniforms
             self.accept = runner.DeviceGreedy(st, self.accept.target, self.accept.draft_tokens)
@@ -106,6 +118,8 @@ class Step:
         if self.fuse is not None:
             self.fuse.run()
         self.accept.run()
+        if self.routing is not None:
+            self.routing()
 
 
 def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling"):
@@ -150,7 +164,7 @@ def main():
     cfg = W.CONFIGS[args.workload]
     a = W.make_attn_inputs(cfg, seed=args.seed)
     ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
-    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse) for _ in range(max(1, args.copies))]
+    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse, args.routing) for _ in range(max(1, args.copies))]
     torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -234,7 +248,8 @@ def main():
         "launch_mode": "eager" if graphs is None else "hip_graph_replay",
         "accept_mode": args.accept_mode,
         "calls_per_step": ["spec_verify_attn"] + (["spec_fuse_drafts"] if copies[0].fuse is not None else []) +
-                          ["spec_accept" if args.accept_mode == "sampling" else "spec_accept_greedy"],
+                          ["spec_accept" if args.accept_mode == "sampling" else "spec_accept_greedy"] +
+                          (["spec_routing_scores"] if copies[0].routing is not None else []),
         "config": {"workload": cfg.name, "batch": cfg.batch, "draft_tokens_per_step": tokens,
                    "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
                    "context": str(cfg.ctx), "draft": str(cfg.draft), "vocab": cfg.vocab,

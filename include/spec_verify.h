@@ -211,6 +211,34 @@ int32_t spec_accept_greedy(
     int32_t* row_argmax,         /* optional [total_nodes + B]: g of every target row  */
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------
+ * spec_routing_scores
+ *
+ * The routing-score update that follows acceptance (Section 4.1, Eq. 1 and Eq. 2).
+ * For request b, drafter n and draft position i < k_len[b]:
+ *   d = cos(H[out_tokens[b,i]], H[draft_tokens[b,i,n]])  if i < accept_len[b]  (the
+ *       positions whose draft was accepted; out_tokens as written by spec_accept),
+ *       0 otherwise;
+ *   scores[b,n] = (1/k_len[b]) sum_i c d / (c d + (1-c)(1-d)),  c = conf[b,i,n].
+ * H = rows of the embedding table.  Where the paper is silent: a negative cosine
+ * counts as 0, a zero row gives cosine 0, a term whose denominator is not positive
+ * (c=1,d=0 or c=0,d=1) is 0, k_len[b] = 0 gives 0.  Token ids are clamped to [0, V).
+ * k_max <= 64, N <= 16.  No workspace.
+ * ---------------------------------------------------------------------------- */
+int32_t spec_routing_scores(
+    int32_t B, int32_t k_max, int32_t N,
+    int32_t V, int32_t E,        /* embedding table shape                              */
+    const int32_t* k_len,        /* [B] valid positions per request, <= k_max          */
+    const float* conf,           /* [B, k_max, N] in [0,1]                             */
+    const int32_t* draft_tokens, /* [B, k_max, N]                                      */
+    const int32_t* accept_len,   /* [B]                                                */
+    const int32_t* out_tokens,   /* [B, out_stride]                                    */
+    int32_t out_stride,
+    const void* embedding,       /* [V, E]                                             */
+    int32_t embedding_dtype,     /* spec_dtype                                         */
+    float* scores,               /* [B, N]                                             */
+    void* stream);
+
 const char* spec_strerror(int32_t status);
 
 /* Library/ABI version, bumped when a signature changes. */

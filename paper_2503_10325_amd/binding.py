@@ -23,6 +23,7 @@ EXPORTS = [
     "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
     "spec_accept_workspace_size", "spec_accept",
     "spec_accept_greedy_workspace_size", "spec_accept_greedy",
+    "spec_routing_scores",
     "spec_strerror", "spec_abi_version",
 ]
 
@@ -70,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.spec_accept_greedy_workspace_size.argtypes = [i32] * 3
         L.spec_accept_greedy.restype = i32
         L.spec_accept_greedy.argtypes = [i32] * 4 + [vp] * 4 + [i32, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.spec_routing_scores.restype = i32
+        L.spec_routing_scores.argtypes = [i32] * 5 + [vp] * 5 + [i32, vp, i32, vp, vp]
         L.spec_accept.restype = i32
         L.spec_accept.argtypes = ([i32] * 5 + [vp] * 4 + [i32, vp, i32, i32, vp, f32] + [vp] * 4 + [i32]
                                   + [vp] * 3 + [sz, vp])
@@ -184,3 +187,15 @@ def spec_accept_greedy(B, total_nodes, max_nodes_per_req, node_offsets, parent, 
                                   _ptr(row_argmax), _ptr(workspace), ws_bytes, _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_accept_greedy", rc)
+
+
+def spec_routing_scores(k_len, conf, draft_tokens, accept_len, out_tokens, embedding, scores, stream=None) -> None:
+    """conf, draft_tokens [B, k_max, N]; out_tokens [B, out_stride] int32; embedding [V, E] (bf16 or fp32);
+    scores [B, N] fp32 (device tensors)."""
+    B, k_max, N = conf.shape
+    V, E = embedding.shape
+    rc = lib().spec_routing_scores(B, k_max, N, V, E, _ptr(k_len), _ptr(conf), _ptr(draft_tokens), _ptr(accept_len),
+                                   _ptr(out_tokens), out_tokens.shape[1], _ptr(embedding), _dtype_code(embedding),
+                                   _ptr(scores), _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_routing_scores", rc)

@@ -166,4 +166,22 @@ int32_t spec_accept_greedy(int32_t B, int32_t V, int32_t total_nodes, int32_t ma
   return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
 }
 
+int32_t spec_routing_scores(int32_t B, int32_t k_max, int32_t N, int32_t V, int32_t E, const int32_t* k_len,
+                            const float* conf, const int32_t* draft_tokens, const int32_t* accept_len,
+                            const int32_t* out_tokens, int32_t out_stride, const void* embedding,
+                            int32_t embedding_dtype, float* scores, void* stream) {
+  if (B < 0 || k_max < 0 || N < 0 || V <= 0 || E <= 0 || out_stride < 0) return SPEC_ERR_SHAPE;
+  if (k_max > 64 || N > 16) return SPEC_ERR_UNSUPPORTED;
+  if (embedding_dtype != SPEC_BF16 && embedding_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
+  if (B == 0 || N == 0) return SPEC_OK;
+  if (!k_len || !accept_len || !scores) return SPEC_ERR_NULL;
+  if (k_max > 0 && (!conf || !draft_tokens || !out_tokens || !embedding)) return SPEC_ERR_NULL;
+  RoutingArgs a{};
+  a.B = B; a.k_max = k_max; a.N = N; a.V = V; a.E = E; a.k_len = k_len; a.conf = conf; a.draft_tokens = draft_tokens;
+  a.accept_len = accept_len; a.out_tokens = out_tokens; a.out_stride = out_stride; a.embedding = embedding;
+  a.e_dtype = embedding_dtype; a.scores = scores;
+  launch_routing_scores(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -50,6 +50,19 @@ struct GreedyArgs {
 size_t greedy_workspace_bytes(int B, int total_nodes, int V);
 void launch_accept_greedy(const GreedyArgs& a, hipStream_t stream);
 
+// ---- routing.hip ------------------------------------------------------------------
+struct RoutingArgs {
+  int B, k_max, N, V, E;
+  const int32_t* k_len;
+  const float* conf;
+  const int32_t* draft_tokens;
+  const int32_t* accept_len;
+  const int32_t* out_tokens; int out_stride;
+  const void* embedding; int e_dtype;
+  float* scores;
+};
+void launch_routing_scores(const RoutingArgs& a, hipStream_t stream);
+
 // ---- fuse.hip ---------------------------------------------------------------------
 struct FuseArgs {
   int B, k_max, N, V;

@@ -337,6 +337,34 @@ def make_accept_inputs(cfg: VerifyConfig, seed: int = 0, st: Optional[DraftStruc
     return AcceptInputs(cfg, st, tgt, dq, q_row, toks, u_acc, u_res, None)
 
 
+@dataclasses.dataclass
+class RoutingInputs:
+    """Inputs of the routing-score update: what the drafters proposed, what was accepted, and the
+    target model's token-embedding table (synthetic stand-in, N(0,1) rounded to bf16)."""
+    k_len: np.ndarray          # [B] int32
+    conf: np.ndarray           # [B, k_max, N] float32
+    draft_tokens: np.ndarray   # [B, k_max, N] int32
+    accept_len: np.ndarray     # [B] int32
+    out_tokens: np.ndarray     # [B, k_max + 1] int32
+    embedding: np.ndarray      # [V, E] bf16 bits
+
+
+def make_routing_inputs(batch: int, k_max: int, n_drafters: int, vocab: int, emb_dim: int, seed: int = 0,
+                        name: str = "routing", agree: float = 0.5) -> RoutingInputs:
+    """Seeded synthetic case: ragged draft lengths, acceptance lengths anywhere in 0..k, accepted
+    tokens that a drafter's own token matches with probability `agree`."""
+    r = _rng(seed, name, "routing")
+    k_len = r.integers(1, k_max + 1, size=batch).astype(np.int32) if k_max > 0 else np.zeros(batch, np.int32)
+    accept_len = (r.integers(0, k_max + 1, size=batch) % (k_len + 1)).astype(np.int32)
+    conf = r.beta(2.0, 2.0, size=(batch, k_max, n_drafters)).astype(np.float32)
+    out_tokens = r.integers(0, vocab, size=(batch, k_max + 1)).astype(np.int32)
+    draft_tokens = r.integers(0, vocab, size=(batch, k_max, n_drafters)).astype(np.int32)
+    same = r.random((batch, k_max, n_drafters)) < agree
+    draft_tokens = np.where(same, out_tokens[:, :k_max, None], draft_tokens).astype(np.int32)
+    embedding = _normal_bf16(_rng(seed, name, "embedding"), (vocab, emb_dim))
+    return RoutingInputs(k_len, conf, draft_tokens, accept_len, out_tokens, embedding)
+
+
 def attention_bytes_flops(cfg: VerifyConfig, st: DraftStructure) -> Tuple[int, int]:
     """Bytes the attention step must move (K and V of every cached position once per KV
     head, Q in, bf16 O out) and its floating-point operation count (QK^T and PV)."""
