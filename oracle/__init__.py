@@ -207,3 +207,14 @@ def routing_scores(k_len, conf, draft_tokens, accept_len, out_tokens, embedding)
     if rc != 0:
         raise RuntimeError(f"oracle_routing_scores failed: {rc}")
     return scores
+
+
+def adaptive_speculation(gamma, gamma_max_total, in_batch=None):
+    """Algorithm 2's AdaptiveSpeculation.  Returns (gamma_out [R] int32, total over the batch)."""
+    gamma = _i32(gamma)
+    mask = None if in_batch is None else _i32(in_batch)
+    out = np.zeros_like(gamma)
+    fn = lib().oracle_adaptive_speculation
+    fn.restype = ctypes.c_longlong
+    total = fn(ctypes.c_int(gamma.shape[0]), _p(gamma), _p(mask), ctypes.c_longlong(int(gamma_max_total)), _p(out))
+    return out, int(total)

@@ -28,6 +28,10 @@
  *                         a draft token is kept when it is the target's most likely
  *                         token at its position; the first mismatch is replaced by
  *                         that most likely token.
+ *   oracle_adaptive_speculation - the draft-length adjustment that precedes
+ *                         verification (Algorithm 2, AdaptiveSpeculation): while the
+ *                         batch's draft tokens exceed the verification budget, the
+ *                         request with the most draft tokens gives one up.
  *   oracle_routing_scores - the routing-score update that follows acceptance
  *                         (Section 4.1, Eq. 1 and Eq. 2): per drafter, the mean over
  *                         draft positions of the normalised harmonic combination of
@@ -433,4 +437,35 @@ int oracle_routing_scores(int B, int k_max, int N, int V, int E, const int32_t* 
     }
   }
   return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* adaptive speculation                                                        */
+/* ------------------------------------------------------------------------- */
+/*
+ * Algorithm 2, AdaptiveSpeculation(B, Gamma_max): while sum_i b_i gamma_i > Gamma_max, take
+ * j = argmax_i gamma_i over the requests of the batch (b_i = 1) and decrement gamma_j.
+ * Readings where the paper is silent: ties go to the lowest index; a request keeps at least one
+ * draft token (the constraint gamma_i >= 1 of the batch formulation, Section 4.3), so the loop
+ * also stops when every request of the batch is at 1; requests outside the batch are untouched.
+ * in_batch may be NULL (all requests are in the batch).  Returns the final sum over the batch.
+ */
+long long oracle_adaptive_speculation(int R, const int32_t* gamma_in, const int32_t* in_batch,
+                                      long long gamma_max_total, int32_t* gamma_out) {
+  long long sum = 0;
+  for (int i = 0; i < R; ++i) {
+    gamma_out[i] = gamma_in[i];
+    if (!in_batch || in_batch[i]) sum += gamma_in[i];
+  }
+  while (sum > gamma_max_total) {
+    int j = -1;
+    for (int i = 0; i < R; ++i) {
+      if (in_batch && !in_batch[i]) continue;
+      if (j < 0 || gamma_out[i] > gamma_out[j]) j = i;
+    }
+    if (j < 0 || gamma_out[j] <= 1) break;
+    gamma_out[j] -= 1;
+    sum -= 1;
+  }
+  return sum;
 }
