@@ -239,6 +239,26 @@ int32_t spec_routing_scores(
     float* scores,               /* [B, N]                                             */
     void* stream);
 
+/* ------------------------------------------------------------------------------
+ * spec_adaptive_speculation
+ *
+ * AdaptiveSpeculation of Algorithm 2 (Section 4.3): the draft lengths gamma_i of the
+ * requests of a batch are cut until their sum fits the verification budget: while
+ * sum_i gamma_i > gamma_max_total, the request with the largest gamma_i (lowest index
+ * on ties) gives up one token.  Every request keeps at least one token (gamma_i >= 1
+ * in the batch formulation), so the sum may stay above the budget when all are at 1.
+ * Requests with in_batch[i] == 0 are copied unchanged and do not count.  gamma_out must
+ * not overlap gamma_in.  The result equals the sequential loop exactly.  Any R; one launch.
+ * ---------------------------------------------------------------------------- */
+int32_t spec_adaptive_speculation(
+    int32_t R,                   /* requests in the pool                               */
+    const int32_t* gamma_in,     /* [R] draft tokens asked for                         */
+    const int32_t* in_batch,     /* [R] b_i, or NULL = every request is in the batch   */
+    int64_t gamma_max_total,     /* Gamma_max                                          */
+    int32_t* gamma_out,          /* [R]                                                */
+    int64_t* total_out,          /* optional [1]: sum of gamma_out over the batch      */
+    void* stream);
+
 const char* spec_strerror(int32_t status);
 
 /* Library/ABI version, bumped when a signature changes. */

@@ -23,7 +23,7 @@ EXPORTS = [
     "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
     "spec_accept_workspace_size", "spec_accept",
     "spec_accept_greedy_workspace_size", "spec_accept_greedy",
-    "spec_routing_scores",
+    "spec_routing_scores", "spec_adaptive_speculation",
     "spec_strerror", "spec_abi_version",
 ]
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.spec_accept_greedy.argtypes = [i32] * 4 + [vp] * 4 + [i32, vp, vp, i32, vp, vp, vp, sz, vp]
         L.spec_routing_scores.restype = i32
         L.spec_routing_scores.argtypes = [i32] * 5 + [vp] * 5 + [i32, vp, i32, vp, vp]
+        L.spec_adaptive_speculation.restype = i32
+        L.spec_adaptive_speculation.argtypes = [i32, vp, vp, ctypes.c_int64, vp, vp, vp]
         L.spec_accept.restype = i32
         L.spec_accept.argtypes = ([i32] * 5 + [vp] * 4 + [i32, vp, i32, i32, vp, f32] + [vp] * 4 + [i32]
                                   + [vp] * 3 + [sz, vp])
@@ -199,3 +201,11 @@ def spec_routing_scores(k_len, conf, draft_tokens, accept_len, out_tokens, embed
                                    _ptr(scores), _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_routing_scores", rc)
+
+
+def spec_adaptive_speculation(gamma_in, gamma_max_total, gamma_out, in_batch=None, total_out=None, stream=None) -> None:
+    """gamma_in, gamma_out [R] int32, in_batch [R] int32 or None, total_out [1] int64 or None (device tensors)."""
+    rc = lib().spec_adaptive_speculation(gamma_in.shape[0], _ptr(gamma_in), _ptr(in_batch), int(gamma_max_total),
+                                         _ptr(gamma_out), _ptr(total_out), _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_adaptive_speculation", rc)

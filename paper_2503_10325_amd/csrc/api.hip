@@ -184,4 +184,14 @@ int32_t spec_routing_scores(int32_t B, int32_t k_max, int32_t N, int32_t V, int3
   return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
 }
 
+int32_t spec_adaptive_speculation(int32_t R, const int32_t* gamma_in, const int32_t* in_batch,
+                                  int64_t gamma_max_total, int32_t* gamma_out, int64_t* total_out, void* stream) {
+  if (R < 0) return SPEC_ERR_SHAPE;
+  if (R == 0) return SPEC_OK;
+  if (!gamma_in || !gamma_out) return SPEC_ERR_NULL;
+  launch_adaptive_speculation(R, gamma_in, in_batch, static_cast<long long>(gamma_max_total), gamma_out,
+                              reinterpret_cast<long long*>(total_out), static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -63,6 +63,10 @@ struct RoutingArgs {
 };
 void launch_routing_scores(const RoutingArgs& a, hipStream_t stream);
 
+// ---- adaptive.hip -----------------------------------------------------------------
+void launch_adaptive_speculation(int R, const int32_t* gamma_in, const int32_t* in_batch, long long budget,
+                                 int32_t* gamma_out, long long* total_out, hipStream_t stream);
+
 // ---- fuse.hip ---------------------------------------------------------------------
 struct FuseArgs {
   int B, k_max, N, V;
