@@ -102,25 +102,6 @@ constexpr int kWalkWaves = kWalkThreads / kWave;
 constexpr int kMaxNodes = 64;
 constexpr int kMaxBlocksPerSeg = 256;      // vocabularies up to 16 * 256 * 512 = 2M tokens
 
-struct RowStat {
-  float m;    // largest logit of the row
-  double z;   // sum_v 2^((l_v - m) c)
-};
-
-__device__ __forceinline__ RowStat merge_stats(const SegStat* __restrict__ stats, int64_t row, int nseg, float c) {
-  float M = -INFINITY;
-  for (int s = 0; s < nseg; ++s) M = fmaxf(M, stats[row * nseg + s].m);
-  double Z = 0.0;
-  for (int s = 0; s < nseg; ++s) {
-    const SegStat st = stats[row * nseg + s];
-    if (st.m != -INFINITY)
-      Z += st.z * exp2(static_cast<double>(st.m - M) * static_cast<double>(c));
-  }
-  RowStat r;
-  r.m = M; r.z = Z;
-  return r;
-}
-
 struct WalkRows {
   const void* t_base; int t_dtype; int64_t t_off; float t_m; double t_invz;   // target row
   const void* q_base; int q_dtype; int64_t q_off; float q_m; double q_invz;   // draft row
