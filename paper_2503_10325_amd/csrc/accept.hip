@@ -9,6 +9,8 @@
 //   accept_walk_kernel  one workgroup per request: the sequential walk; every full
 //                       pass over a row pair (residual mass, inverse-CDF search) is
 //                       spread over the workgroup's 16 waves.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -27,9 +29,12 @@ template <bool VEC>
 __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
     const void* __restrict__ t_base, int t_dtype, int n_t_rows,
     const void* __restrict__ q_base, int q_dtype, int n_q_rows,
-    int V, float c, int nseg, SegStat* __restrict__ stats) {
+    int V, float c, int nseg, SegStat* __restrict__ stats, unsigned* __restrict__ zero_words, int n_zero) {
   const int seg = blockIdx.x;
   const int row = blockIdx.y;
+  // side job of the first workgroup: clear the flags the walk kernel's workgroups exchange
+  if (seg == 0 && row == 0)
+    for (int i = threadIdx.x; i < n_zero; i += kStatThreads) zero_words[i] = 0u;
   const void* base = t_base;
   int dtype = t_dtype;
   int64_t r = row;
@@ -80,7 +85,8 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
 }
 
 void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void* q_base, int q_dtype,
-                      int n_q_rows, int V, float c, SegStat* stats, hipStream_t stream) {
+                      int n_q_rows, int V, float c, SegStat* stats, hipStream_t stream, unsigned* zero_words,
+                      int n_zero) {
   const int rows = n_t_rows + n_q_rows;
   if (rows <= 0 || V <= 0) return;
   const int nseg = stats_segments(V);
@@ -88,10 +94,10 @@ void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void*
   const bool vec = (V % 8 == 0);
   if (vec)
     hipLaunchKernelGGL(row_stats_kernel<true>, grid, dim3(kStatThreads), 0, stream, t_base, t_dtype,
-                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats);
+                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero);
   else
     hipLaunchKernelGGL(row_stats_kernel<false>, grid, dim3(kStatThreads), 0, stream, t_base, t_dtype,
-                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats);
+                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero);
 }
 
 // ----------------------------------------------------------------------------------
@@ -153,6 +159,110 @@ __device__ __forceinline__ void unpack_bf16x8(u32x4 r, float (&x)[8]) {
   x[4] = bf16_lo(r[2]); x[5] = bf16_hi(r[2]); x[6] = bf16_lo(r[3]); x[7] = bf16_hi(r[3]);
 }
 
+// Sum of the level-L weights over [e_begin, e_end) (a multiple of 512 tokens wide, nit blocks) by one
+// wave; the result is in every lane.  FAST: 16-byte aligned bf16 rows, four 512-token blocks in flight.
+template <bool VEC, bool FAST>
+__device__ __forceinline__ double wave_pass_sum(const WalkRows& R, int L, const float* __restrict__ inv_Rf,
+                                                int e_begin, int e_end, int nit, int V, float c, int lane) {
+  double acc = 0.0;
+  if constexpr (FAST) {
+    const uint16_t* tp = static_cast<const uint16_t*>(R.t_base) + R.t_off;
+    const uint16_t* qp = static_cast<const uint16_t*>(R.q_base) + R.q_off;
+    for (int it0 = 0; it0 < nit; it0 += 4) {
+      u32x4 rp[4], rq[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e0 = min(e_begin + (it0 + u) * 512 + lane * 8, V - 8);     // clamped; masked below
+        rp[u] = *reinterpret_cast<const u32x4*>(tp + e0);
+        if (L > 0) rq[u] = *reinterpret_cast<const u32x4*>(qp + e0);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int it = it0 + u;
+        if (it < nit) {
+          const int e0 = e_begin + it * 512 + lane * 8;
+          float lp[8], lq[8];
+          unpack_bf16x8(rp[u], lp);
+          if (L > 0) unpack_bf16x8(rq[u], lq);
+          float w[8];
+          weights_from(R, lp, lq, e0 < e_end ? 8 : 0, c, L, inv_Rf, w);
+          float lsf = 0.f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) lsf += w[j];
+          acc += static_cast<double>(lsf);
+        }
+      }
+    }
+  } else {
+    for (int it = 0; it < nit; ++it) {
+      const int e0 = e_begin + it * 512 + lane * 8;
+      float lsf = 0.f;
+      if (e0 < e_end) {
+        float w[8];
+        weights8<VEC>(R, e0, V, c, L, inv_Rf, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lsf += w[j];
+      }
+      acc += static_cast<double>(lsf);
+    }
+  }
+  return wave_sum(acc);
+}
+
+// ---- helper workgroups -----------------------------------------------------------------------
+// A full pass over a large vocabulary is bound by the vector ALU of the one compute unit that runs
+// the request's walk (two exp2 per class).  For such vocabularies every request gets up to three
+// helper workgroups on other compute units: the vocabulary is cut into 16 x (1 + helpers) contiguous
+// wave segments, the master publishes what a pass needs, each helper sums its 16 segments and hands
+// the sums back, and the master goes on as if it had 64 waves.  The partition is static and the
+// grid (masters first, then helpers) is at most one workgroup per compute unit, so every workgroup
+// becomes resident without waiting for another; helpers only ever wait for their master, the master
+// only for its helpers, and every wait is bounded.
+// Everything exchanged goes through relaxed device-scope atomic accesses (they bypass the
+// non-coherent cache levels for exactly these words; acquire/release would write back and
+// invalidate the whole L2 of the XCD on every poll and evict the logit rows the passes re-read).
+// Order between a payload and its flag: the payload's stores have completed (vmcnt 0) before the
+// flag is written.
+template <typename T> __device__ __forceinline__ T ld_dev(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ void st_dev(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+constexpr int kMaxHelpers = 3;
+
+// What a helper wave hands back: the sum of its segment and the pass it belongs to.  The wave
+// writes the sum, waits for that store to complete, then writes the pass number; the master reads
+// the 16 bytes with one load (one access to one cache line), so a matching pass number always comes
+// with its sum and a hand-off costs a single trip.
+struct __attribute__((aligned(16))) PartSlot {
+  double sum;
+  unsigned seq;
+  unsigned pad;
+};
+__device__ __forceinline__ PartSlot ld_slot(const PartSlot* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  PartSlot r;
+  r.sum = __builtin_bit_cast(double, (static_cast<unsigned long long>(v[1]) << 32) | v[0]);
+  r.seq = v[2];
+  r.pad = 0;
+  return r;
+}
+constexpr unsigned kDone = 0xffffffffu;    // pass number that tells the helpers to leave
+constexpr int kSpinLimit = 4000000;        // bounded waits (seconds): a stuck wait gives up and flags the request
+
+struct PassDesc {            // written by the master, published by `seq` (pass number, from 1)
+  unsigned seq;
+  int level;
+  long long t_off, q_off;
+  float t_m, q_m;
+  double t_invz, q_invz;
+  float inv_R[kMaxNodes];
+};
+
 struct AcceptParams {
   int B, V, n_t_rows, n_q_rows, nseg;
   const int32_t* node_offsets;
@@ -169,27 +279,89 @@ struct AcceptParams {
   int32_t* stop_node;
   float* dbg_ratio;
   const SegStat* stats;
+  int helpers;              // helper workgroups per request (0: the master works alone)
+  PassDesc* desc;           // [B]
+  PartSlot* part;           // [B][helpers][16] wave sums handed back by the helpers
 };
 
 // FAST: 16-byte aligned rows with both logit matrices in bf16 (the default layout): the full
 // passes keep four 512-token blocks in flight per wave.
 template <bool VEC, bool FAST>
 __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams P) {
-  const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int S = P.helpers;
+  const int vwaves = kWalkWaves * (1 + S);                 // wave segments the vocabulary is cut into
+  __shared__ float sh_inv_Rf[kMaxNodes];     // 1 / R_k, fp32, for the per-class passes
+  __shared__ unsigned sh_seq;
+  __shared__ int sh_flag;
+
+  // =============================== helper workgroup ===============================
+  if (static_cast<int>(blockIdx.x) >= P.B) {
+    const int idx = blockIdx.x - P.B;
+    const int hb = idx % P.B, h = idx / P.B;               // request, helper number 0..S-1
+    const int seg_w = (((P.V + vwaves - 1) / vwaves) + 511) / 512 * 512;
+    const int e_begin = ((h + 1) * kWalkWaves + wave) * seg_w;
+    const int e_end = min(P.V, e_begin + seg_w);
+    const int nit = e_end > e_begin ? (e_end - e_begin + 511) / 512 : 0;
+    PassDesc* desc = P.desc + hb;
+    unsigned last_seq = 0;
+    // Roles inside the loop are per wave, never per lane: with `if (tid == 0)` at the end of one
+    // iteration and at the start of the next, the compiler routes the other lanes of wave 0 around
+    // both, and they reach the workgroup barrier without lane 0 - a partial wave at s_barrier.
+    // All 64 lanes of wave 0 poll (one coalesced load) and store the same words.
+    for (;;) {
+      if (wave == 0) {
+        int spins = 0, fin = 0;
+        unsigned seq = 0;
+        for (;;) {
+          seq = ld_dev(&desc->seq);                          // kDone once the master needs no more passes
+          if (seq == kDone) { fin = 1; break; }
+          if (seq > last_seq) break;
+          __builtin_amdgcn_s_sleep(1);
+          if (++spins > kSpinLimit) { fin = 1; break; }      // the master never came: leave
+        }
+        sh_seq = seq;
+        sh_flag = fin;
+      }
+      __syncthreads();
+      if (sh_flag) return;
+      const unsigned seq = sh_seq;
+      WalkRows R;
+      R.t_base = P.target; R.t_dtype = P.t_dtype; R.q_base = P.draft_q; R.q_dtype = P.q_dtype;
+      R.q_is_probs = (P.q_kind == 1); R.have_q = 1;
+      const int level = ld_dev(&desc->level);
+      R.t_off = ld_dev(&desc->t_off); R.q_off = ld_dev(&desc->q_off);
+      R.t_m = ld_dev(&desc->t_m); R.q_m = ld_dev(&desc->q_m);
+      R.t_invz = ld_dev(&desc->t_invz); R.q_invz = ld_dev(&desc->q_invz);
+      sh_inv_Rf[tid & (kMaxNodes - 1)] = ld_dev(&desc->inv_R[tid & (kMaxNodes - 1)]);    // every thread, same values
+      __syncthreads();
+      // The master rewrites the descriptor only after this helper has handed back the sums of pass
+      // `seq`, so the copy above is consistent.
+      const double acc = wave_pass_sum<VEC, FAST>(R, min(max(level, 0), kMaxNodes), sh_inv_Rf, e_begin, e_end, nit, P.V, P.c, lane);
+      PartSlot* slot = P.part + (static_cast<int64_t>(hb) * S + h) * kWalkWaves + wave;
+      st_dev(&slot->sum, acc);                   // all lanes of the wave store the same words
+      wait_stores();
+      st_dev(&slot->seq, seq);
+      last_seq = seq;
+      __syncthreads();                           // sh_inv_Rf and sh_seq are rewritten in the next round
+    }
+  }
+
+  // =============================== master workgroup ===============================
+  const int b = blockIdx.x;
   const int o = P.node_offsets[b];
   int n = P.node_offsets[b + 1] - o;
   n = n < 0 ? 0 : (n > kMaxNodes ? kMaxNodes : n);
   const int64_t trow0 = static_cast<int64_t>(o) + b;
   const int V = P.V;
   const float c = P.c;
-  // contiguous vocab segment of each wave, a multiple of 512 tokens
-  const int seg_w = (((V + kWalkWaves - 1) / kWalkWaves) + 511) / 512 * 512;
+  // contiguous vocab segment of each wave (the master's 16 and the helpers'), a multiple of 512 tokens
+  const int seg_w = (((V + vwaves - 1) / vwaves) + 511) / 512 * 512;
 
-  __shared__ double sh_wave_sum[kWalkWaves];
+  __shared__ double sh_wave_sum[kWalkWaves * (1 + kMaxHelpers)];
+  __shared__ int sh_fail;
   __shared__ double sh_blk[kMaxBlocksPerSeg];   // sums of the 512-token blocks of the segment the draw falls in
   __shared__ double sh_inv_R[kMaxNodes];     // 1 / R_k for the scalar accept tests
-  __shared__ float sh_inv_Rf[kMaxNodes];     // the same, fp32, for the per-class passes
   __shared__ int sh_token;
   // per-request tables filled once, in parallel, so that the walk itself touches no global memory
   __shared__ float sh_tm[kMaxNodes + 1];       // target local row i: max logit
@@ -214,6 +386,8 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     sh_u[tid] = P.u_accept[o + tid];
     if (P.dbg_ratio) P.dbg_ratio[o + tid] = __builtin_nanf("");
   }
+  if (tid < kMaxNodes) sh_inv_Rf[tid] = 0.f;
+  if (tid == 0) sh_fail = 0;
   __syncthreads();
   // (2) in one round trip: the two logits of every drafted token (last wave) and the merged
   // statistics of the n+1 target rows and n draft rows (groups of 16 lanes, one segment each)
@@ -268,56 +442,43 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   const int e_end = min(V, e_begin + seg_w);
   const int nit = e_end > e_begin ? (e_end - e_begin + 511) / 512 : 0;
 
-  // One full pass at residual level L: per-wave sums to LDS, returns the total.
+  // One full pass at residual level L: per-wave sums (the master's and the helpers') to LDS, returns
+  // the total.
+  unsigned pass_no = 0;
   auto full_pass = [&](int L) -> double {
-    double acc = 0.0;
     __syncthreads();                 // previous readers of the sums are done
-    if constexpr (FAST) {
-      const uint16_t* tp = static_cast<const uint16_t*>(R.t_base) + R.t_off;
-      const uint16_t* qp = static_cast<const uint16_t*>(R.q_base) + R.q_off;
-      for (int it0 = 0; it0 < nit; it0 += 4) {
-        u32x4 rp[4], rq[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int e0 = min(e_begin + (it0 + u) * 512 + lane * 8, V - 8);     // clamped; masked below
-          rp[u] = *reinterpret_cast<const u32x4*>(tp + e0);
-          if (L > 0) rq[u] = *reinterpret_cast<const u32x4*>(qp + e0);
+    ++pass_no;
+    if (S > 0 && wave == 0) {          // all lanes of wave 0 store the same words (no per-lane role, see the helper loop)
+      PassDesc* desc = P.desc + b;
+      st_dev(&desc->level, L);
+      st_dev(&desc->t_off, static_cast<long long>(R.t_off)); st_dev(&desc->q_off, static_cast<long long>(R.q_off));
+      st_dev(&desc->t_m, R.t_m); st_dev(&desc->q_m, R.q_m);
+      st_dev(&desc->t_invz, R.t_invz); st_dev(&desc->q_invz, R.q_invz);
+      for (int k = 0; k < L && k < kMaxNodes; ++k) st_dev(&desc->inv_R[k], sh_inv_Rf[k]);
+      wait_stores();
+      st_dev(&desc->seq, pass_no);
+    }
+    const double acc = wave_pass_sum<VEC, FAST>(R, L, sh_inv_Rf, e_begin, e_end, nit, V, c, lane);
+    if (lane == 0) sh_wave_sum[wave] = acc;
+    if (S > 0) {
+      if (wave == 0) {               // lane l watches helper wave l (the last one again for lanes beyond)
+        const int n_slots = S * kWalkWaves;                     // <= 48
+        const int my = min(lane, n_slots - 1);
+        const PartSlot* slot = P.part + static_cast<int64_t>(b) * n_slots + my;
+        int spins = 0;
+        PartSlot got;
+        for (;;) {
+          got = ld_slot(slot);
+          if (__all(got.seq == pass_no)) break;
+          __builtin_amdgcn_s_sleep(1);
+          if (++spins > kSpinLimit) { sh_fail = 1; break; }
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int it = it0 + u;
-          if (it < nit) {
-            const int e0 = e_begin + it * 512 + lane * 8;
-            float lp[8], lq[8];
-            unpack_bf16x8(rp[u], lp);
-            if (L > 0) unpack_bf16x8(rq[u], lq);
-            float w[8];
-            weights_from(R, lp, lq, e0 < e_end ? 8 : 0, c, L, sh_inv_Rf, w);
-            float lsf = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) lsf += w[j];
-            acc += static_cast<double>(lsf);
-          }
-        }
-      }
-    } else {
-      for (int it = 0; it < nit; ++it) {
-        const int e0 = e_begin + it * 512 + lane * 8;
-        float lsf = 0.f;
-        if (e0 < e_end) {
-          float w[8];
-          weights8<VEC>(R, e0, V, c, L, sh_inv_Rf, w);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) lsf += w[j];
-        }
-        acc += static_cast<double>(lsf);
+        sh_wave_sum[kWalkWaves + my] = got.sum;                 // lanes beyond n_slots repeat the last slot's value
       }
     }
-    acc = wave_sum(acc);
-    if (lane == 0) sh_wave_sum[wave] = acc;
     __syncthreads();
     double tot = 0.0;
-    for (int w = 0; w < kWalkWaves; ++w) tot += sh_wave_sum[w];
+    for (int w = 0; w < vwaves; ++w) tot += sh_wave_sum[w];
     return tot;
   };
 
@@ -379,16 +540,17 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     }
     // no child, or every child rejected: draw from the level's weights by inverse CDF
     if (sums_level != level) { total = full_pass(level); sums_level = level; }
+    if (S > 0 && wave == 0) st_dev(&P.desc[b].seq, kDone);  // no more passes: the helpers may leave
     const double target = u_res * total;
     int ws = -1;
     double before = 0.0;
-    for (int w = 0; w < kWalkWaves; ++w) {
+    for (int w = 0; w < vwaves; ++w) {
       const double sw = sh_wave_sum[w];
       if (before + sw > target) { ws = w; break; }
       before += sw;
     }
-    if (ws < 0) {                    // rounding left no crossing: last wave with positive mass
-      for (int w = kWalkWaves - 1; w >= 0; --w) if (sh_wave_sum[w] > 0.0) { ws = w; break; }
+    if (ws < 0) {                    // rounding left no crossing: last wave segment with positive mass
+      for (int w = vwaves - 1; w >= 0; --w) if (sh_wave_sum[w] > 0.0) { ws = w; break; }
       if (ws < 0) ws = 0;
       before = 0.0;
       for (int w = 0; w < ws; ++w) before += sh_wave_sum[w];
@@ -471,15 +633,33 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     break;
   }
   if (tid == 0) {
-    P.accept_len[b] = depth;
+    if (S > 0) st_dev(&P.desc[b].seq, kDone);
+    P.accept_len[b] = sh_fail ? -1 : depth;       // -1: a wait on a helper workgroup gave up (never expected)
     if (P.stop_node) P.stop_node[b] = cur;
   }
   for (int i = depth + 1 + tid; i < P.out_stride; i += kWalkThreads) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + i] = -1;
 }
 
-size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V) {
+// Workspace: [row statistics][helper protocol: pass descriptors, hand-back slots (zeroed by the
+// statistics kernel)]
+struct AcceptLayout {
+  size_t words_off, n_zero_words, desc_off, part_off, total;
+};
+
+static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  AcceptLayout l;
   const size_t rows = static_cast<size_t>(total_nodes) + B + n_q_rows;
-  return rows * stats_segments(V) * sizeof(SegStat) + 256;
+  l.words_off = up(rows * stats_segments(V) * sizeof(SegStat));
+  l.desc_off = l.words_off;
+  l.part_off = l.desc_off + up(static_cast<size_t>(B) * sizeof(PassDesc));
+  l.total = l.part_off + up(static_cast<size_t>(B) * kMaxHelpers * kWalkWaves * sizeof(PartSlot)) + 256;
+  l.n_zero_words = (l.total - 256 - l.words_off) / sizeof(unsigned);     // flags, descriptors and hand-back slots
+  return l;
+}
+
+size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V) {
+  return accept_layout(B, total_nodes, n_q_rows, V).total;
 }
 
 void launch_accept(const AcceptArgs& a, hipStream_t stream) {
@@ -487,8 +667,12 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   const float c = kLog2e / a.temperature;
   const int n_t_rows = a.total_nodes + a.B;
   const int n_q_stat_rows = (a.q_kind == 0) ? a.n_q_rows : 0;
-  SegStat* stats = static_cast<SegStat*>(a.workspace);
-  launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream);
+  const AcceptLayout lay = accept_layout(a.B, a.total_nodes, a.n_q_rows, a.V);
+  unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+  SegStat* stats = reinterpret_cast<SegStat*>(ws);
+  unsigned* words = reinterpret_cast<unsigned*>(ws + lay.words_off);      // start of the zeroed region
+  launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream, words,
+                   static_cast<int>(lay.n_zero_words));
   AcceptParams P;
   P.B = a.B; P.V = a.V; P.n_t_rows = n_t_rows; P.n_q_rows = a.n_q_rows > 0 ? a.n_q_rows : 1; P.nseg = stats_segments(a.V);
   P.node_offsets = a.node_offsets; P.parent = a.parent; P.draft_tokens = a.draft_tokens;
@@ -497,11 +681,33 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   P.q_row = a.q_row; P.c = c; P.u_accept = a.u_accept; P.u_resample = a.u_resample;
   P.accept_len = a.accept_len; P.out_tokens = a.out_tokens; P.out_stride = a.out_stride;
   P.stop_node = a.stop_node; P.dbg_ratio = a.dbg_ratio; P.stats = stats;
+  P.desc = reinterpret_cast<PassDesc*>(ws + lay.desc_off);
+  P.part = reinterpret_cast<PartSlot*>(ws + lay.part_off);
+  // Helpers pay when a pass is long against a hand-off between compute units (a few microseconds):
+  // vocabularies of 64k classes and more; masters plus helpers stay within one workgroup per compute unit.
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+      n_cu = 256;
+  }
+  int helpers = 0;
+  if (a.V >= 65536) {
+    helpers = n_cu / a.B - 1;
+    helpers = helpers < 0 ? 0 : (helpers > kMaxHelpers ? kMaxHelpers : helpers);
+  }
+  if (const char* e = getenv("SPECV_WALK_HELPERS")) {       // development knob
+    const int v = atoi(e);
+    if (v >= 0 && v <= kMaxHelpers && a.B * (1 + v) <= n_cu) helpers = v;
+  }
+  P.helpers = helpers;
+  const dim3 grid(a.B * (1 + helpers));
   const bool vec = (a.V % 8 == 0);
   const bool fast = vec && a.V >= 8 && a.t_dtype == kBF16 && a.q_dtype == kBF16 && a.q_kind == 0;
-  if (fast) hipLaunchKernelGGL((accept_walk_kernel<true, true>), dim3(a.B), dim3(kWalkThreads), 0, stream, P);
-  else if (vec) hipLaunchKernelGGL((accept_walk_kernel<true, false>), dim3(a.B), dim3(kWalkThreads), 0, stream, P);
-  else hipLaunchKernelGGL((accept_walk_kernel<false, false>), dim3(a.B), dim3(kWalkThreads), 0, stream, P);
+  if (fast) hipLaunchKernelGGL((accept_walk_kernel<true, true>), grid, dim3(kWalkThreads), 0, stream, P);
+  else if (vec) hipLaunchKernelGGL((accept_walk_kernel<true, false>), grid, dim3(kWalkThreads), 0, stream, P);
+  else hipLaunchKernelGGL((accept_walk_kernel<false, false>), grid, dim3(kWalkThreads), 0, stream, P);
 }
 
 }  // namespace specv
