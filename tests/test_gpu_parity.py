@@ -170,6 +170,20 @@ def test_accept_matches_oracle(rt, name):
     assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
 
 
+@pytest.mark.parametrize("helpers", ["0", "1", "2", "3"])
+def test_accept_helper_workgroups(rt, helpers, monkeypatch):
+    """Large vocabularies split every full pass over helper workgroups; any helper count (the library reads
+    the development knob at call time) must reproduce the oracle's decisions."""
+    monkeypatch.setenv("SPECV_WALK_HELPERS", helpers)
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=6, vocab=70001 if helpers == "2" else 128256)
+    ai = W.make_accept_inputs(cfg, seed=8)
+    got, ref = _run_accept(rt, cfg, ai)
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+    assert (got["accept_len"] >= 0).all()
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+
+
 def test_accept_draft_equals_target_accepts_all(rt):
     cfg = W.scaled(C["c1_llama2_7b"], batch=5, vocab=8000)
     ai = W.make_accept_inputs(cfg, seed=9, draft_equals_target=True)
