@@ -80,3 +80,38 @@ def test_accept_and_fuse_validation_needs_no_gpu():
     assert fuse(B=0) == 0
     assert sv.spec_fuse_drafts_workspace_size(2, 3, 4, 100, 0) == 0
     assert sv.spec_fuse_drafts_workspace_size(2, 3, 4, 100, 1) > 0
+
+
+def test_greedy_routing_adaptive_validation_needs_no_gpu():
+    L = sv.lib()
+    null = ctypes.c_void_p(0)
+
+    def greedy(B=2, V=100, total=4, maxn=2, stride=3, tdt=0):
+        return L.spec_accept_greedy(B, V, total, maxn, null, null, null, null, tdt, null, null, stride, null, null,
+                                    null, 0, null)
+
+    assert greedy() == -1                      # NULL tensors
+    assert greedy(V=0) == -2
+    assert greedy(maxn=65, stride=66) == -3
+    assert greedy(stride=2) == -2
+    assert greedy(tdt=5) == -3
+    assert greedy(B=40000, total=40000) == -3  # more rows than one launch takes
+    assert greedy(B=0) == 0
+    assert sv.spec_accept_greedy_workspace_size(2, 4, 100) >= 256
+
+    def routing(B=2, k=3, N=4, V=100, E=64, stride=4, edt=0):
+        return L.spec_routing_scores(B, k, N, V, E, null, null, null, null, null, stride, null, edt, null, null)
+
+    assert routing() == -1
+    assert routing(E=0) == -2
+    assert routing(k=65) == -3
+    assert routing(N=17) == -3
+    assert routing(edt=3) == -3
+    assert routing(B=0) == 0
+
+    def adaptive(R=4):
+        return L.spec_adaptive_speculation(R, null, null, 10, null, null, null)
+
+    assert adaptive() == -1
+    assert adaptive(R=-1) == -2
+    assert adaptive(R=0) == 0
