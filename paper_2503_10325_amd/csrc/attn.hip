@@ -1026,14 +1026,17 @@ static AttnPlan make_plan(const AttnArgs& a) {
   // which only pays when lengths differ: the caller's total-token hint against batch x longest
   // request says whether they do.
   const bool ragged = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok;
-  int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 32 : 0;
+  int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 36 : 0;
   if (const char* e = getenv("SPECV_ATTN_TAU")) {         // development knob for sweeps (0: grid-mapped launch)
     const int v = atoi(e);
     if (token_split && a.B <= kPlanMaxB && v >= 0 && v <= 255) tau = v;
   }
   if (getenv("SPECV_ATTN_JOBS")) tau = 0;
   if (tau > 0) {
-    const int64_t max_tiles = (max_tok + kTile - 1) / kTile;     // tiles of the longest request when one wave streams them all
+    // most tiles one wave can have to stream: the longest request, shared by as many waves as the
+    // largest declared row count leaves per query block (requests with fewer rows get more waves)
+    const int min_slice = max_rows <= 32 ? 4 : (max_rows <= 64 ? 2 : 1);
+    const int64_t max_tiles = ((max_tok + kTile - 1) / kTile + min_slice - 1) / min_slice;
     const int64_t mc = (max_tiles + tau - 1) / tau;
     p.tau = tau;
     p.max_chunks = static_cast<int>(mc < 1 ? 1 : (mc > kListMaxChunks ? kListMaxChunks : mc));
