@@ -228,9 +228,15 @@ def main():
     accept_bytes = n_logit_rows * cfg.vocab * 2
     # the attention kernel the library's plan picks for this shape (all query rows that share a KV head)
     max_rows = int(a.st.n.max()) * (cfg.n_q_heads // cfg.n_kv_heads)
-    attn_kernel = (f"attn_stream_kernel<{cfg.head_dim}> (token-split, one workgroup per request x KV head x context chunk)"
-                   if max_rows <= 128 else
-                   f"attn_rows_kernel<{cfg.head_dim},8> (row-split, 8 waves share each K/V tile)")
+    total_tok = int((a.st.ctx_len.astype(np.int64) + a.st.n).sum())
+    ragged = cfg.batch <= 128 and total_tok * 100 < 85 * cfg.batch * a.max_pages * 16     # the library's own rule
+    if max_rows > 128:
+        attn_kernel = f"attn_rows_kernel<{cfg.head_dim},8> (row-split, 8 waves share each K/V tile)"
+    elif ragged:
+        attn_kernel = (f"attn_stream_list_kernel<{cfg.head_dim}> (token-split body, device-built work list sorted by "
+                       f"length, 2 persistent workgroups per CU)")
+    else:
+        attn_kernel = f"attn_stream_kernel<{cfg.head_dim}> (token-split, one workgroup per request x KV head x context chunk)"
     achieved = attn_bytes / attn_s / 1e9
     out = {
         "metric": METRIC,
