@@ -252,7 +252,7 @@ __device__ __forceinline__ PartSlot ld_slot(const PartSlot* p) {
   return r;
 }
 constexpr unsigned kDone = 0xffffffffu;    // pass number that tells the helpers to leave
-constexpr int kSpinLimit = 4000000;        // bounded waits (seconds): a stuck wait gives up and flags the request
+constexpr int kSpinLimit = 4000000;        // a helper whose master never shows up leaves after this many polls (seconds)
 
 struct PassDesc {            // written by the master, published by `seq` (pass number, from 1)
   unsigned seq;
@@ -280,6 +280,7 @@ struct AcceptParams {
   float* dbg_ratio;
   const SegStat* stats;
   int helpers;              // helper workgroups per request (0: the master works alone)
+  int patience;             // polls a master spends on its helpers before it sums their segments itself
   PassDesc* desc;           // [B]
   PartSlot* part;           // [B][helpers][16] wave sums handed back by the helpers
 };
@@ -335,8 +336,10 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
       R.t_invz = ld_dev(&desc->t_invz); R.q_invz = ld_dev(&desc->q_invz);
       sh_inv_Rf[tid & (kMaxNodes - 1)] = ld_dev(&desc->inv_R[tid & (kMaxNodes - 1)]);    // every thread, same values
       __syncthreads();
-      // The master rewrites the descriptor only after this helper has handed back the sums of pass
-      // `seq`, so the copy above is consistent.
+      // Normally the master rewrites the descriptor only after this helper has handed back the sums of
+      // pass `seq`.  A master that ran out of patience may already be at a later pass: the copy above
+      // can then mix two passes (every field is still a valid value of one of them, so all reads stay
+      // in bounds) and the sum written below carries the old pass number, which the master ignores.
       const double acc = wave_pass_sum<VEC, FAST>(R, min(max(level, 0), kMaxNodes), sh_inv_Rf, e_begin, e_end, nit, P.V, P.c, lane);
       PartSlot* slot = P.part + (static_cast<int64_t>(hb) * S + h) * kWalkWaves + wave;
       st_dev(&slot->sum, acc);                   // all lanes of the wave store the same words
@@ -359,7 +362,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   const int seg_w = (((V + vwaves - 1) / vwaves) + 511) / 512 * 512;
 
   __shared__ double sh_wave_sum[kWalkWaves * (1 + kMaxHelpers)];
-  __shared__ int sh_fail;
+  __shared__ unsigned long long sh_missing;
   __shared__ double sh_blk[kMaxBlocksPerSeg];   // sums of the 512-token blocks of the segment the draw falls in
   __shared__ double sh_inv_R[kMaxNodes];     // 1 / R_k for the scalar accept tests
   __shared__ int sh_token;
@@ -387,7 +390,6 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     if (P.dbg_ratio) P.dbg_ratio[o + tid] = __builtin_nanf("");
   }
   if (tid < kMaxNodes) sh_inv_Rf[tid] = 0.f;
-  if (tid == 0) sh_fail = 0;
   __syncthreads();
   // (2) in one round trip: the two logits of every drafted token (last wave) and the merged
   // statistics of the n+1 target rows and n draft rows (groups of 16 lanes, one segment each)
@@ -467,13 +469,32 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
         const PartSlot* slot = P.part + static_cast<int64_t>(b) * n_slots + my;
         int spins = 0;
         PartSlot got;
+        bool up;
         for (;;) {
           got = ld_slot(slot);
-          if (__all(got.seq == pass_no)) break;
+          up = got.seq == pass_no;
+          if (__all(up)) break;
+          if (++spins > P.patience) break;                      // helpers not there (yet): see below
           __builtin_amdgcn_s_sleep(1);
-          if (++spins > kSpinLimit) { sh_fail = 1; break; }
         }
-        sh_wave_sum[kWalkWaves + my] = got.sum;                 // lanes beyond n_slots repeat the last slot's value
+        if (up) sh_wave_sum[kWalkWaves + my] = got.sum;         // lanes beyond n_slots repeat the last slot
+        const unsigned long long missing = __ballot(!up) & ((1ull << n_slots) - 1ull);
+        if (lane == 0) sh_missing = missing;
+      }
+      __syncthreads();
+      // Segments whose helper wave has not answered within the patience (its workgroup may not be
+      // resident yet when other kernels fill the GPU) are summed here instead: the walk never
+      // depends on a helper making progress.  A late answer is ignored (its pass number is old).
+      unsigned long long miss = sh_missing;
+      for (int k = 0; miss; ++k) {
+        const int j = __ffsll(static_cast<long long>(miss)) - 1;
+        miss &= miss - 1;
+        if ((k & (kWalkWaves - 1)) != wave) continue;
+        const int hb_begin = (kWalkWaves + j) * seg_w;
+        const int hb_end = min(V, hb_begin + seg_w);
+        const int hb_nit = hb_end > hb_begin ? (hb_end - hb_begin + 511) / 512 : 0;
+        const double a2 = wave_pass_sum<VEC, FAST>(R, L, sh_inv_Rf, hb_begin, hb_end, hb_nit, V, c, lane);
+        if (lane == 0) sh_wave_sum[kWalkWaves + j] = a2;
       }
     }
     __syncthreads();
@@ -634,7 +655,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   }
   if (tid == 0) {
     if (S > 0) st_dev(&P.desc[b].seq, kDone);
-    P.accept_len[b] = sh_fail ? -1 : depth;       // -1: a wait on a helper workgroup gave up (never expected)
+    P.accept_len[b] = depth;
     if (P.stop_node) P.stop_node[b] = cur;
   }
   for (int i = depth + 1 + tid; i < P.out_stride; i += kWalkThreads) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + i] = -1;
@@ -702,6 +723,11 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
     if (v >= 0 && v <= kMaxHelpers && a.B * (1 + v) <= n_cu) helpers = v;
   }
   P.helpers = helpers;
+  P.patience = 400;                                          // a few hundred microseconds
+  if (const char* e = getenv("SPECV_WALK_PATIENCE")) {      // development knob: 0 makes every pass fall back
+    const int v = atoi(e);
+    if (v >= 0 && v <= 1000000) P.patience = v;
+  }
   const dim3 grid(a.B * (1 + helpers));
   const bool vec = (a.V % 8 == 0);
   const bool fast = vec && a.V >= 8 && a.t_dtype == kBF16 && a.q_dtype == kBF16 && a.q_kind == 0;

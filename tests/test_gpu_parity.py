@@ -184,6 +184,19 @@ def test_accept_helper_workgroups(rt, helpers, monkeypatch):
     assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
 
 
+def test_accept_master_without_helper_answers(rt, monkeypatch):
+    """With no patience at all the master never waits for a helper and sums every segment itself (what it
+    does when helper workgroups are late because other kernels fill the GPU); late answers are ignored."""
+    monkeypatch.setenv("SPECV_WALK_HELPERS", "3")
+    monkeypatch.setenv("SPECV_WALK_PATIENCE", "0")
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=5)
+    ai = W.make_accept_inputs(cfg, seed=13)
+    got, ref = _run_accept(rt, cfg, ai)
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+
+
 def test_accept_draft_equals_target_accepts_all(rt):
     cfg = W.scaled(C["c1_llama2_7b"], batch=5, vocab=8000)
     ai = W.make_accept_inputs(cfg, seed=9, draft_equals_target=True)
