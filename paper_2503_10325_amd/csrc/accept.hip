@@ -6,9 +6,10 @@
 // Two kernels:
 //   row_stats_kernel    one workgroup per (row, vocab segment): segment maximum and
 //                       sum of 2^((l-m)c).  Pure streaming, HBM-bound.
-//   accept_walk_kernel  one workgroup per request: the sequential walk; every full
+//   accept_walk_kernel  one master workgroup per request: the sequential walk; every full
 //                       pass over a row pair (residual mass, inverse-CDF search) is
-//                       spread over the workgroup's 16 waves.
+//                       spread over the workgroup's 16 waves and, for large vocabularies,
+//                       over the waves of up to three helper workgroups.
 #include <stdlib.h>
 
 #include "common.h"

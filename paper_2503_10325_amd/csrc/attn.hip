@@ -2,16 +2,21 @@
 // bf16 KV cache (committed context + their draft ancestors), Section 2.1 / 4.2 of the
 // paper (parallel verification with a tree-attention mask).
 //
-// Work decomposition.  One workgroup (4 waves) per (request, KV head, context chunk,
-// row group).  All n*G query rows that share a KV head are processed together so every
-// K/V byte is fetched once per KV head.  Inside the workgroup every wave streams its own
-// 32-token tiles (2 cache pages): coalesced 16-byte global loads -> registers -> the
-// wave's private LDS tile -> MFMA operands.  S^T = K Q^T and O^T = V^T P^T run on
-// v_mfma_f32_32x32x16_bf16 with the tokens as the M dimension, so each lane owns one
-// query column and the online-softmax statistics need a single cross-lane exchange.
-// V is transposed on its way into LDS (token pairs packed with v_perm).  The waves'
-// partial results are merged through LDS; when a request spans several chunks the
-// workgroup writes an unnormalised partial and attn_combine_kernel merges the chunks.
+// Work decomposition.  All n*G query rows that share a KV head are processed together so every
+// K/V byte is fetched once per KV head; long requests are cut into context chunks whose
+// unnormalised partial results attn_combine_kernel merges (split-KV).  Two bodies:
+//   token-split (stream_item, <= 128 rows per KV head): a 4-wave workgroup per (request, KV head,
+//     chunk); every wave streams its own 32-token tiles (2 cache pages): coalesced 16-byte global
+//     loads -> registers -> the wave's private LDS tile -> MFMA operands; waves that share a
+//     32-row query block merge through LDS.  Launched grid-mapped (attn_stream_kernel) or, for
+//     small ragged batches, from a work list built on the device and sorted by length
+//     (attn_stream_list_kernel).
+//   row-split (attn_rows_kernel, more rows): the waves of a workgroup stage 64-token
+//     tiles together (double-buffered LDS) and each owns one block of 32 query rows.
+// In both, S^T = K Q^T and O^T = V^T P^T run on v_mfma_f32_32x32x16_bf16 with the tokens as the
+// M dimension, so each lane owns one query column and the online-softmax statistics need a
+// single exchange between the half-waves.  V is transposed on its way into LDS (token pairs
+// packed with v_perm).
 #include <stdlib.h>
 
 #include "common.h"
