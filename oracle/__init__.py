@@ -218,3 +218,21 @@ def adaptive_speculation(gamma, gamma_max_total, in_batch=None):
     fn.restype = ctypes.c_longlong
     total = fn(ctypes.c_int(gamma.shape[0]), _p(gamma), _p(mask), ctypes.c_longlong(int(gamma_max_total)), _p(out))
     return out, int(total)
+
+
+def compact_kv(k_pool, v_pool, block_table, ctx_len, q_offsets, parent, stop_node, page_size=16):
+    """Accepted-path compaction.  Pools [num_pages, Hkv, page, D] uint16 are modified IN PLACE.
+    Returns new_len [B] = ctx_len + depth of the accepted path."""
+    assert k_pool.dtype == np.uint16 and v_pool.dtype == np.uint16 and k_pool.flags["C_CONTIGUOUS"] and v_pool.flags["C_CONTIGUOUS"]
+    _, Hkv, page, D = k_pool.shape
+    assert page == page_size
+    block_table, ctx_len, q_offsets, stop_node = _i32(block_table), _i32(ctx_len), _i32(q_offsets), _i32(stop_node)
+    par = None if parent is None else _i32(parent)
+    B = ctx_len.shape[0]
+    new_len = np.zeros(B, dtype=np.int32)
+    rc = lib().oracle_compact_kv(ctypes.c_int(B), ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(page),
+                                 ctypes.c_int(block_table.shape[1]), _p(k_pool), _p(v_pool), _p(block_table),
+                                 _p(ctx_len), _p(q_offsets), _p(par), _p(stop_node), _p(new_len))
+    if rc != 0:
+        raise RuntimeError(f"oracle_compact_kv failed: {rc}")
+    return new_len

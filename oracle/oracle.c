@@ -32,6 +32,11 @@
  *                         verification (Algorithm 2, AdaptiveSpeculation): while the
  *                         batch's draft tokens exceed the verification budget, the
  *                         request with the most draft tokens gives one up.
+ *   oracle_compact_kv    - after a draft tree has been verified, the K/V entries of the
+ *                         accepted path are moved to consecutive cache positions so
+ *                         that the next step sees an ordinary linear context (the paper
+ *                         only says verified drafts return to the request pool,
+ *                         Section 4.1; the data movement is this build's reading).
  *   oracle_routing_scores - the routing-score update that follows acceptance
  *                         (Section 4.1, Eq. 1 and Eq. 2): per drafter, the mean over
  *                         draft positions of the normalised harmonic combination of
@@ -468,4 +473,50 @@ long long oracle_adaptive_speculation(int R, const int32_t* gamma_in, const int3
     sum -= 1;
   }
   return sum;
+}
+
+/* ------------------------------------------------------------------------- */
+/* accepted-path compaction of the paged KV cache                              */
+/* ------------------------------------------------------------------------- */
+/*
+ * Request b holds its n[b] draft nodes at logical positions ctx_len[b] + j of its paged cache.
+ * With stop_node[b] the last accepted node (-1: none) the accepted path is the chain of ancestors
+ * root .. stop_node; its d-th node (d = 0 ..) moves from position ctx + node to position ctx + d,
+ * for both pools and every KV head.  All sources are read before anything is written.
+ * Pools: [num_pages, Hkv, page, D] 16-bit elements; block_table [B, max_pages].
+ * Returns the depth of the path in new_len[b] = ctx_len[b] + depth (optional).
+ */
+int oracle_compact_kv(int B, int Hkv, int D, int page, int max_pages, uint16_t* k_pool, uint16_t* v_pool,
+                      const int32_t* block_table, const int32_t* ctx_len, const int32_t* q_offsets,
+                      const int32_t* parent, const int32_t* stop_node, int32_t* new_len) {
+  for (int b = 0; b < B; ++b) {
+    const int o = q_offsets[b], n = q_offsets[b + 1] - o;
+    int path[64], depth = 0;
+    for (int a = stop_node[b]; a >= 0 && a < n && depth < 64; a = parent ? parent[o + a] : a - 1) path[depth++] = a;
+    /* path[] runs leaf -> root; position d from the root is path[depth - 1 - d] */
+    const size_t row = (size_t)D;
+    uint16_t* tmp = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)(depth > 0 ? depth : 1) * 2 * Hkv * row);
+    if (!tmp) return -7;
+    for (int d = 0; d < depth; ++d) {
+      const int pos = ctx_len[b] + path[depth - 1 - d];
+      const int64_t pg = block_table[(int64_t)b * max_pages + pos / page];
+      for (int h = 0; h < Hkv; ++h) {
+        const int64_t src = ((pg * Hkv + h) * page + pos % page) * (int64_t)D;
+        memcpy(tmp + ((size_t)(d * 2 + 0) * Hkv + h) * row, k_pool + src, sizeof(uint16_t) * row);
+        memcpy(tmp + ((size_t)(d * 2 + 1) * Hkv + h) * row, v_pool + src, sizeof(uint16_t) * row);
+      }
+    }
+    for (int d = 0; d < depth; ++d) {
+      const int pos = ctx_len[b] + d;
+      const int64_t pg = block_table[(int64_t)b * max_pages + pos / page];
+      for (int h = 0; h < Hkv; ++h) {
+        const int64_t dst = ((pg * Hkv + h) * page + pos % page) * (int64_t)D;
+        memcpy(k_pool + dst, tmp + ((size_t)(d * 2 + 0) * Hkv + h) * row, sizeof(uint16_t) * row);
+        memcpy(v_pool + dst, tmp + ((size_t)(d * 2 + 1) * Hkv + h) * row, sizeof(uint16_t) * row);
+      }
+    }
+    free(tmp);
+    if (new_len) new_len[b] = ctx_len[b] + depth;
+  }
+  return 0;
 }
