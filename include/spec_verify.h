@@ -259,6 +259,32 @@ int32_t spec_adaptive_speculation(
     int64_t* total_out,          /* optional [1]: sum of gamma_out over the batch      */
     void* stream);
 
+/* ------------------------------------------------------------------------------
+ * spec_compact_kv
+ *
+ * After a draft tree has been verified, moves the K/V entries of the accepted path to
+ * consecutive cache positions, so that the next step sees an ordinary linear context.
+ * The paper only says that verified drafts return to the request pool (Section 4.1);
+ * this data movement is what a paged cache with tree drafts needs for that.  Draft
+ * node j of request b lives at logical position ctx_len[b] + j; the accepted path is
+ * the chain of ancestors root .. stop_node[b] (as written by spec_accept or
+ * spec_accept_greedy; -1 = nothing accepted); its d-th node moves to position
+ * ctx_len[b] + d, in both pools, for every KV head.  Linear drafts need no move and are
+ * left untouched.  Pools and block table as in spec_verify_attn; the pools are modified
+ * in place.  new_len[b] = ctx_len[b] + path length.  head_dim 64 or 128, page_size 16,
+ * at most 64 nodes per request.
+ * ---------------------------------------------------------------------------- */
+int32_t spec_compact_kv(
+    int32_t B, int32_t num_kv_heads, int32_t head_dim, int32_t page_size, int32_t max_pages_per_req,
+    void* k_pool, void* v_pool,  /* [num_pages, Hkv, page_size, D] bf16, modified      */
+    const int32_t* block_table,  /* [B, max_pages_per_req]                             */
+    const int32_t* ctx_len,      /* [B]                                                */
+    const int32_t* q_offsets,    /* [B+1] prefix sums of n[b]                          */
+    const int32_t* parent,       /* [total_q] or NULL = linear chains                  */
+    const int32_t* stop_node,    /* [B] last accepted node, -1 = none                  */
+    int32_t* new_len,            /* optional [B]                                       */
+    void* stream);
+
 const char* spec_strerror(int32_t status);
 
 /* Library/ABI version, bumped when a signature changes. */

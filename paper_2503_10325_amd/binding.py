@@ -23,7 +23,7 @@ EXPORTS = [
     "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
     "spec_accept_workspace_size", "spec_accept",
     "spec_accept_greedy_workspace_size", "spec_accept_greedy",
-    "spec_routing_scores", "spec_adaptive_speculation",
+    "spec_routing_scores", "spec_adaptive_speculation", "spec_compact_kv",
     "spec_strerror", "spec_abi_version",
 ]
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.spec_routing_scores.argtypes = [i32] * 5 + [vp] * 5 + [i32, vp, i32, vp, vp]
         L.spec_adaptive_speculation.restype = i32
         L.spec_adaptive_speculation.argtypes = [i32, vp, vp, ctypes.c_int64, vp, vp, vp]
+        L.spec_compact_kv.restype = i32
+        L.spec_compact_kv.argtypes = [i32] * 5 + [vp] * 9
         L.spec_accept.restype = i32
         L.spec_accept.argtypes = ([i32] * 5 + [vp] * 4 + [i32, vp, i32, i32, vp, f32] + [vp] * 4 + [i32]
                                   + [vp] * 3 + [sz, vp])
@@ -209,3 +211,13 @@ def spec_adaptive_speculation(gamma_in, gamma_max_total, gamma_out, in_batch=Non
                                          _ptr(gamma_out), _ptr(total_out), _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_adaptive_speculation", rc)
+
+
+def spec_compact_kv(k_pool, v_pool, block_table, ctx_len, q_offsets, parent, stop_node, new_len=None, stream=None) -> None:
+    """Pools [num_pages, Hkv, 16, D] bf16 device tensors (modified in place); the rest int32 device tensors."""
+    _, Hkv, page, D = k_pool.shape
+    rc = lib().spec_compact_kv(ctx_len.shape[0], Hkv, D, page, block_table.shape[1], _ptr(k_pool), _ptr(v_pool),
+                               _ptr(block_table), _ptr(ctx_len), _ptr(q_offsets), _ptr(parent), _ptr(stop_node),
+                               _ptr(new_len), _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_compact_kv", rc)

@@ -194,4 +194,22 @@ int32_t spec_adaptive_speculation(int32_t R, const int32_t* gamma_in, const int3
   return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
 }
 
+int32_t spec_compact_kv(int32_t B, int32_t num_kv_heads, int32_t head_dim, int32_t page_size,
+                        int32_t max_pages_per_req, void* k_pool, void* v_pool, const int32_t* block_table,
+                        const int32_t* ctx_len, const int32_t* q_offsets, const int32_t* parent,
+                        const int32_t* stop_node, int32_t* new_len, void* stream) {
+  if (B < 0 || num_kv_heads <= 0 || max_pages_per_req < 0) return SPEC_ERR_SHAPE;
+  if ((head_dim != 64 && head_dim != 128) || page_size != 16) return SPEC_ERR_UNSUPPORTED;
+  if (B > 65535 || num_kv_heads > 65535) return SPEC_ERR_UNSUPPORTED;
+  if (B == 0) return SPEC_OK;
+  if (!k_pool || !v_pool || !block_table || !ctx_len || !q_offsets || !stop_node) return SPEC_ERR_NULL;
+  CompactArgs a{};
+  a.B = B; a.Hkv = num_kv_heads; a.D = head_dim; a.max_pages = max_pages_per_req;
+  a.k_pool = static_cast<uint16_t*>(k_pool); a.v_pool = static_cast<uint16_t*>(v_pool);
+  a.block_table = block_table; a.ctx_len = ctx_len; a.q_offsets = q_offsets; a.parent = parent;
+  a.stop_node = stop_node; a.new_len = new_len;
+  launch_compact_kv(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
 }  // extern "C"

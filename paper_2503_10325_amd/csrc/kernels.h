@@ -68,6 +68,20 @@ void launch_routing_scores(const RoutingArgs& a, hipStream_t stream);
 void launch_adaptive_speculation(int R, const int32_t* gamma_in, const int32_t* in_batch, long long budget,
                                  int32_t* gamma_out, long long* total_out, hipStream_t stream);
 
+// ---- compact.hip ------------------------------------------------------------------
+struct CompactArgs {
+  int B, Hkv, D, max_pages;
+  uint16_t* k_pool;
+  uint16_t* v_pool;
+  const int32_t* block_table;
+  const int32_t* ctx_len;
+  const int32_t* q_offsets;
+  const int32_t* parent;
+  const int32_t* stop_node;
+  int32_t* new_len;
+};
+void launch_compact_kv(const CompactArgs& a, hipStream_t stream);
+
 // ---- fuse.hip ---------------------------------------------------------------------
 struct FuseArgs {
   int B, k_max, N, V;
