@@ -236,3 +236,26 @@ def compact_kv(k_pool, v_pool, block_table, ctx_len, q_offsets, parent, stop_nod
     if rc != 0:
         raise RuntimeError(f"oracle_compact_kv failed: {rc}")
     return new_len
+
+
+def lm_head(hidden, weight, temperature=1.0, want_exact=False):
+    """LM-head projection with row statistics.  hidden [rows, d] and weight [V, d] as bf16 bit
+    patterns (uint16).  Returns dict(logits uint16 [rows, V], row_max [rows], row_z [rows],
+    exact fp64 [rows, V] when asked for)."""
+    hidden = np.ascontiguousarray(hidden, dtype=np.uint16)
+    weight = np.ascontiguousarray(weight, dtype=np.uint16)
+    rows, d = hidden.shape
+    V, d2 = weight.shape
+    assert d == d2
+    logits = np.zeros((rows, V), dtype=np.uint16)
+    exact = np.zeros((rows, V), dtype=np.float64) if want_exact else None
+    row_max = np.zeros(rows, dtype=np.float64)
+    row_z = np.zeros(rows, dtype=np.float64)
+    rc = lib().oracle_lm_head(ctypes.c_int(rows), ctypes.c_int(d), ctypes.c_int(V), _p(hidden), _p(weight),
+                              ctypes.c_double(temperature), _p(logits), _p(exact), _p(row_max), _p(row_z))
+    if rc != 0:
+        raise RuntimeError(f"oracle_lm_head failed: {rc}")
+    out = dict(logits=logits, row_max=row_max, row_z=row_z)
+    if want_exact:
+        out["exact"] = exact
+    return out

@@ -37,6 +37,11 @@
  *                         that the next step sees an ordinary linear context (the paper
  *                         only says verified drafts return to the request pool,
  *                         Section 4.1; the data movement is this build's reading).
+ *   oracle_lm_head      - the projection that produces the logits the acceptance step reads
+ *                         (Section 3.1: verification on the target model is dominated by
+ *                         matrix-matrix products): logits = hidden x weight^T, rounded to
+ *                         bf16, with each row's softmax statistics (maximum and
+ *                         sum of exp((l - max)/T) over the rounded logits).
  *   oracle_routing_scores - the routing-score update that follows acceptance
  *                         (Section 4.1, Eq. 1 and Eq. 2): per drafter, the mean over
  *                         draft positions of the normalised harmonic combination of
@@ -517,6 +522,53 @@ int oracle_compact_kv(int B, int Hkv, int D, int page, int max_pages, uint16_t* 
     }
     free(tmp);
     if (new_len) new_len[b] = ctx_len[b] + depth;
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* LM head: logits and their per-row softmax statistics                        */
+/* ------------------------------------------------------------------------- */
+/* Nearest bf16 (ties to even) of a finite double, as its 16 bits.  bf16 carries 8 significant
+ * bits; values here are far from its subnormal and overflow ranges. */
+static uint16_t double_to_bf16_bits(double x) {
+  if (x == 0.0) return signbit(x) ? 0x8000u : 0u;
+  int e;
+  const double f = frexp(fabs(x), &e);              /* |x| = f * 2^e, f in [0.5, 1) */
+  const double q = nearbyint(ldexp(f, 8));          /* 8 significant bits, round half to even */
+  const float r = (float)ldexp(q, e - 8);           /* exactly representable */
+  uint32_t u;
+  memcpy(&u, &r, 4);
+  return (uint16_t)((u >> 16) | (signbit(x) ? 0x8000u : 0u));
+}
+
+/*
+ * hidden [rows, d] bf16, weight [V, d] bf16 (one row per vocabulary entry).
+ * exact[r, v]  = sum_k hidden[r, k] * weight[v, k] in fp64 (optional output),
+ * logits[r, v] = bf16(exact[r, v]),
+ * row_max[r]   = max_v logits[r, v],  row_z[r] = sum_v exp((logits[r, v] - row_max[r]) / T).
+ */
+int oracle_lm_head(int rows, int d, int V, const uint16_t* hidden, const uint16_t* weight, double T,
+                   uint16_t* logits, double* exact, double* row_max, double* row_z) {
+  if (rows < 0 || d <= 0 || V <= 0 || !(T > 0.0)) return -2;
+#pragma omp parallel for schedule(static)
+  for (int r = 0; r < rows; ++r) {
+    for (int v = 0; v < V; ++v) {
+      double acc = 0.0;
+      for (int k = 0; k < d; ++k)
+        acc += bf16_to_double(hidden[(int64_t)r * d + k]) * bf16_to_double(weight[(int64_t)v * d + k]);
+      if (exact) exact[(int64_t)r * V + v] = acc;
+      logits[(int64_t)r * V + v] = double_to_bf16_bits(acc);
+    }
+    double m = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+      const double l = bf16_to_double(logits[(int64_t)r * V + v]);
+      if (l > m) m = l;
+    }
+    double z = 0.0;
+    for (int v = 0; v < V; ++v) z += exp((bf16_to_double(logits[(int64_t)r * V + v]) - m) / T);
+    row_max[r] = m;
+    row_z[r] = z;
   }
   return 0;
 }
