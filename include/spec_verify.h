@@ -285,6 +285,52 @@ int32_t spec_compact_kv(
     int32_t* new_len,            /* optional [B]                                       */
     void* stream);
 
+/* ------------------------------------------------------------------------------
+ * spec_lm_head
+ *
+ * The projection that produces the target logits o_i of Section 2.1, the matrix-matrix
+ * product that Section 3.1 identifies as the bulk of verification on the target model,
+ * fused with the first pass of the vocab-wide softmax:
+ *   logits[r, v] = bf16( sum_k hidden[r, k] * weight[v, k] )      (fp32 accumulation)
+ * and, for every row, the statistics (maximum, sum of exp((l - max)/T) per 8192-class
+ * segment of the ROUNDED logits) that spec_accept would otherwise compute by reading
+ * the logits again.  hidden [rows, d_model] and weight [V, d_model] are bf16, row-major
+ * (one weight row per vocabulary entry), 16-byte aligned; d_model a multiple of 128.
+ * Rows are the target rows of spec_accept in its order (rows = total_nodes + B).
+ * target_stats receives spec_row_stats_size(rows, V) bytes in the library's internal
+ * layout: pass the START of the workspace later given to spec_accept_prestats (with
+ * the same temperature), or any device buffer of that size.  Any number of rows up to
+ * 65535; up to 128 rows the weight matrix is read once.
+ * ---------------------------------------------------------------------------- */
+size_t spec_row_stats_size(int32_t rows, int32_t V);
+size_t spec_lm_head_workspace_size(int32_t rows, int32_t V);
+
+int32_t spec_lm_head(
+    int32_t rows, int32_t d_model, int32_t V,
+    const void* hidden,          /* [rows, d_model] bf16                               */
+    const void* weight,          /* [V, d_model] bf16                                  */
+    float temperature,           /* > 0: the T of the statistics                       */
+    void* logits,                /* [rows, V] bf16                                     */
+    void* target_stats,          /* spec_row_stats_size(rows, V) bytes                 */
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------
+ * spec_accept_prestats
+ *
+ * spec_accept for target logits that come from spec_lm_head: same arguments, same
+ * results, but the first spec_row_stats_size(total_nodes + B, V) bytes of workspace
+ * already hold the target rows' statistics (written by spec_lm_head with the same
+ * temperature, V and row order), so only the draft rows are read for statistics.
+ * target_dtype must be SPEC_BF16.  Workspace size as for spec_accept.
+ * ---------------------------------------------------------------------------- */
+int32_t spec_accept_prestats(
+    int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
+    const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+    const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
+    int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
+    const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
+    int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream);
+
 const char* spec_strerror(int32_t status);
 
 /* Library/ABI version, bumped when a signature changes. */

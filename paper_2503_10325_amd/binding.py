@@ -24,6 +24,7 @@ EXPORTS = [
     "spec_accept_workspace_size", "spec_accept",
     "spec_accept_greedy_workspace_size", "spec_accept_greedy",
     "spec_routing_scores", "spec_adaptive_speculation", "spec_compact_kv",
+    "spec_row_stats_size", "spec_lm_head_workspace_size", "spec_lm_head", "spec_accept_prestats",
     "spec_strerror", "spec_abi_version",
 ]
 
@@ -80,6 +81,14 @@ def lib() -> ctypes.CDLL:
         L.spec_accept.restype = i32
         L.spec_accept.argtypes = ([i32] * 5 + [vp] * 4 + [i32, vp, i32, i32, vp, f32] + [vp] * 4 + [i32]
                                   + [vp] * 3 + [sz, vp])
+        L.spec_accept_prestats.restype = i32
+        L.spec_accept_prestats.argtypes = L.spec_accept.argtypes
+        L.spec_row_stats_size.restype = sz
+        L.spec_row_stats_size.argtypes = [i32, i32]
+        L.spec_lm_head_workspace_size.restype = sz
+        L.spec_lm_head_workspace_size.argtypes = [i32, i32]
+        L.spec_lm_head.restype = i32
+        L.spec_lm_head.argtypes = [i32, i32, i32, vp, vp, f32, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -174,6 +183,46 @@ def spec_accept(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_t
                            _ptr(workspace), ws_bytes, _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_accept", rc)
+
+
+def spec_accept_prestats(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_tokens, target_logits,
+                         draft_q, q_kind, q_row, temperature, u_accept, u_resample, accept_len, out_tokens,
+                         stop_node=None, dbg_ratio=None, workspace=None, stream=None) -> None:
+    """spec_accept whose workspace already starts with the target rows' statistics (from spec_lm_head)."""
+    V = target_logits.shape[1]
+    n_q_rows = 0 if draft_q is None else draft_q.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_accept_prestats(B, V, total_nodes, n_q_rows, max_nodes_per_req, _ptr(node_offsets),
+                                    _ptr(parent), _ptr(draft_tokens), _ptr(target_logits),
+                                    _dtype_code(target_logits), _ptr(draft_q),
+                                    SPEC_BF16 if draft_q is None else _dtype_code(draft_q), int(q_kind),
+                                    _ptr(q_row), float(temperature), _ptr(u_accept), _ptr(u_resample),
+                                    _ptr(accept_len), _ptr(out_tokens), out_tokens.shape[1], _ptr(stop_node),
+                                    _ptr(dbg_ratio), _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_accept_prestats", rc)
+
+
+def spec_row_stats_size(rows, V) -> int:
+    return int(lib().spec_row_stats_size(rows, V))
+
+
+def spec_lm_head_workspace_size(rows, V) -> int:
+    return int(lib().spec_lm_head_workspace_size(rows, V))
+
+
+def spec_lm_head(hidden, weight, temperature, logits, target_stats, workspace, stream=None) -> None:
+    """hidden [rows, d_model], weight [V, d_model], logits [rows, V]: bf16 device tensors; target_stats:
+    device tensor of at least spec_row_stats_size(rows, V) bytes (normally the accept workspace)."""
+    rows, d_model = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == d_model and tuple(logits.shape) == (rows, V)
+    assert target_stats.numel() * target_stats.element_size() >= spec_row_stats_size(rows, V)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_lm_head(rows, d_model, V, _ptr(hidden), _ptr(weight), float(temperature), _ptr(logits),
+                            _ptr(target_stats), _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_lm_head", rc)
 
 
 def spec_accept_greedy_workspace_size(B, total_nodes, V) -> int:

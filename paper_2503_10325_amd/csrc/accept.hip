@@ -85,6 +85,10 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
   }
 }
 
+__global__ __launch_bounds__(kStatThreads) void zero_words_kernel(unsigned* __restrict__ words, int n) {
+  for (int i = threadIdx.x; i < n; i += kStatThreads) words[i] = 0u;
+}
+
 void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void* q_base, int q_dtype,
                       int n_q_rows, int V, float c, SegStat* stats, hipStream_t stream, unsigned* zero_words,
                       int n_zero) {
@@ -693,8 +697,18 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
   SegStat* stats = reinterpret_cast<SegStat*>(ws);
   unsigned* words = reinterpret_cast<unsigned*>(ws + lay.words_off);      // start of the zeroed region
-  launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream, words,
-                   static_cast<int>(lay.n_zero_words));
+  if (!a.target_stats_ready) {
+    launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream, words,
+                     static_cast<int>(lay.n_zero_words));
+  } else if (n_q_stat_rows > 0) {
+    // the target rows' entries were written by the LM-head kernel; only the draft rows are left
+    launch_row_stats(a.draft_q, a.q_dtype, n_q_stat_rows, nullptr, 0, 0, a.V, c,
+                     stats + static_cast<size_t>(n_t_rows) * stats_segments(a.V), stream, words,
+                     static_cast<int>(lay.n_zero_words));
+  } else {
+    hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(kStatThreads), 0, stream, words,
+                       static_cast<int>(lay.n_zero_words));
+  }
   AcceptParams P;
   P.B = a.B; P.V = a.V; P.n_t_rows = n_t_rows; P.n_q_rows = a.n_q_rows > 0 ? a.n_q_rows : 1; P.nseg = stats_segments(a.V);
   P.node_offsets = a.node_offsets; P.parent = a.parent; P.draft_tokens = a.draft_tokens;

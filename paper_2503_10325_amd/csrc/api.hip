@@ -105,13 +105,13 @@ size_t spec_accept_workspace_size(int32_t B, int32_t total_nodes, int32_t n_q_ro
   return accept_workspace_bytes(B, total_nodes, n_q_rows, V);
 }
 
-int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
-                    const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
-                    const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
-                    int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
-                    const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
-                    int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes,
-                    void* stream) {
+static int32_t accept_entry(bool prestats, int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
+                            int32_t max_nodes_per_req, const int32_t* node_offsets, const int32_t* parent,
+                            const int32_t* draft_tokens, const void* target_logits, int32_t target_dtype,
+                            const void* draft_q, int32_t q_dtype, int32_t q_kind, const int32_t* q_row,
+                            float temperature, const float* u_accept, const float* u_resample,
+                            int32_t* accept_len, int32_t* out_tokens, int32_t out_stride, int32_t* stop_node,
+                            float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream) {
   if (B < 0 || V <= 0 || total_nodes < 0 || n_q_rows < 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
   if (!(temperature > 0.f)) return SPEC_ERR_SHAPE;
   if (max_nodes_per_req > 64) return SPEC_ERR_UNSUPPORTED;
@@ -133,7 +133,64 @@ int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
   a.draft_q = draft_q; a.q_dtype = q_dtype; a.q_kind = q_kind; a.q_row = q_row; a.temperature = temperature;
   a.u_accept = u_accept; a.u_resample = u_resample; a.accept_len = accept_len; a.out_tokens = out_tokens;
   a.out_stride = out_stride; a.stop_node = stop_node; a.dbg_ratio = dbg_ratio; a.workspace = workspace;
+  a.target_stats_ready = prestats;
   launch_accept(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
+}
+
+int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
+                    const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+                    const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
+                    int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
+                    const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
+                    int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  return accept_entry(false, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent, draft_tokens,
+                      target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature, u_accept,
+                      u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, workspace,
+                      workspace_bytes, stream);
+}
+
+int32_t spec_accept_prestats(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
+                             int32_t max_nodes_per_req, const int32_t* node_offsets, const int32_t* parent,
+                             const int32_t* draft_tokens, const void* target_logits, int32_t target_dtype,
+                             const void* draft_q, int32_t q_dtype, int32_t q_kind, const int32_t* q_row,
+                             float temperature, const float* u_accept, const float* u_resample,
+                             int32_t* accept_len, int32_t* out_tokens, int32_t out_stride, int32_t* stop_node,
+                             float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream) {
+  if (target_dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
+  return accept_entry(true, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent, draft_tokens,
+                      target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature, u_accept,
+                      u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, workspace,
+                      workspace_bytes, stream);
+}
+
+size_t spec_row_stats_size(int32_t rows, int32_t V) {
+  if (rows < 0 || V <= 0) return 0;
+  return row_stats_bytes(rows, V);
+}
+
+size_t spec_lm_head_workspace_size(int32_t rows, int32_t V) {
+  if (rows < 0 || V <= 0) return 0;
+  return lm_head_workspace_bytes(rows, V);
+}
+
+int32_t spec_lm_head(int32_t rows, int32_t d_model, int32_t V, const void* hidden, const void* weight,
+                     float temperature, void* logits, void* target_stats, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  if (rows < 0 || d_model <= 0 || V <= 0) return SPEC_ERR_SHAPE;
+  if (!(temperature > 0.f)) return SPEC_ERR_SHAPE;
+  if (d_model % 128 != 0 || d_model > 65536 || V > 2097152 || rows > 65535) return SPEC_ERR_UNSUPPORTED;
+  if (rows == 0) return SPEC_OK;
+  if (!hidden || !weight || !logits || !target_stats) return SPEC_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(hidden) | reinterpret_cast<uintptr_t>(weight)) & 15u) return SPEC_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(logits) & 7u) || (reinterpret_cast<uintptr_t>(target_stats) & 15u))
+    return SPEC_ERR_SHAPE;
+  if (!workspace || workspace_bytes < lm_head_workspace_bytes(rows, V)) return SPEC_ERR_WORKSPACE;
+  LmHeadArgs a{};
+  a.rows = rows; a.d_model = d_model; a.V = V; a.hidden = hidden; a.weight = weight; a.temperature = temperature;
+  a.logits = logits; a.stats = target_stats; a.workspace = workspace;
+  if (launch_lm_head(a, static_cast<hipStream_t>(stream)) != 0) return SPEC_ERR_LAUNCH;
   return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
 }
 

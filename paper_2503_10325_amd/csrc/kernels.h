@@ -31,9 +31,24 @@ struct AcceptArgs {
   int32_t* stop_node;
   float* dbg_ratio;
   void* workspace;
+  bool target_stats_ready;     // the workspace already starts with the target rows' statistics
 };
 size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V);
 void launch_accept(const AcceptArgs& a, hipStream_t stream);
+
+// ---- lmhead.hip ------------------------------------------------------------------
+struct LmHeadArgs {
+  int rows, d_model, V;
+  const void* hidden;
+  const void* weight;
+  float temperature;
+  void* logits;
+  void* stats;
+  void* workspace;
+};
+size_t lm_head_workspace_bytes(int rows, int V);
+size_t row_stats_bytes(int rows, int V);
+int launch_lm_head(const LmHeadArgs& a, hipStream_t stream);
 
 // ---- greedy.hip -------------------------------------------------------------------
 struct GreedyArgs {

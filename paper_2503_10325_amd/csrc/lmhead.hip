@@ -1,0 +1,271 @@
+// LM-head projection fused with the first pass of the vocab-wide softmax: the matrix product the
+// paper singles out as the bulk of verification on the target model (Section 3.1), producing the
+// logits o_i of Section 2.1 as bf16 together with the per-(row, 8192-class segment) statistics
+// (maximum, sum of 2^((l - max) c)) that the acceptance walk starts from, so that the logits are
+// never read back for that purpose and never exist in fp32.
+//
+//   logits[r, v] = bf16( sum_k hidden[r, k] * weight[v, k] ),  fp32 accumulation on the matrix cores.
+//
+// Vocabulary-as-M tiling: A = 32 weight rows, B = 32 hidden rows, so both operands of
+// v_mfma_f32_32x32x16_bf16 are 16 contiguous bytes per lane of a row-major operand and no
+// transpose is needed anywhere.  One workgroup = 8 waves = 4 vocabulary tiles x 2 halves of the
+// contraction, producing a [128 vocab x 128 rows] block; the two halves are added through LDS.
+// With up to 128 rows (a verification batch) the weight matrix is read exactly once and the kernel
+// is bound by that read; more rows take further row blocks, which are scheduled next to each other
+// on one XCD so that the weight tile is served by that XCD's L2.
+//
+// Both operands are staged global -> registers -> LDS in 64-wide slices of the contraction
+// (rows padded to 144 bytes: conflict-free 16-byte operand reads), one slice ahead, one barrier per
+// slice.  Weight slices are private to their wave; hidden slices are shared by the four waves of a
+// half.
+#include "common.h"
+#include "kernels.h"
+
+namespace specv {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 lm_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float lm_f32x16;
+typedef uint32_t lm_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t lm_u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kLmThreads = 512;
+constexpr int kLmVB = 128;                          // vocabulary entries per workgroup (4 tiles of 32)
+constexpr int kLmRB = 128;                          // hidden rows per workgroup (4 tiles of 32)
+constexpr int kLmKC = 64;                           // contraction slice
+constexpr int kLmPitch = kLmKC * 2 + 16;            // bytes per staged row
+constexpr int kLmHidBuf = kLmRB * kLmPitch;         // one hidden slice
+constexpr int kLmWBuf = 32 * kLmPitch;              // one weight slice of one wave
+constexpr int kLmHidBytes = 2 * 2 * kLmHidBuf;      // 2 halves x 2 buffers
+constexpr int kLmWBytes = 8 * 2 * kLmWBuf;          // 8 waves x 2 buffers
+constexpr int kLmLds = kLmHidBytes + kLmWBytes;     // 147456 bytes
+constexpr int kLmBlocksPerSeg = 8192 / kLmVB;       // block statistics per statistics segment
+static_assert(4 * 64 * 64 * 4 <= kLmHidBytes, "split-K hand-over fits the hidden buffers");
+static_assert(kLmBlocksPerSeg == 64, "one wave merges one segment");
+
+struct LmParams {
+  int rows, K, V;
+  int nvb, nrb, total, per_xcd;
+  float c;
+  const uint16_t* hidden;
+  const uint16_t* weight;
+  uint16_t* logits;
+  float2* bstats;          // [rows][nvb]
+};
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
+  extern __shared__ __align__(16) unsigned char lm_lds[];
+  // consecutive logical blocks (the row blocks of one vocabulary block) on one XCD
+  const int id = blockIdx.x;
+  const int logical = (id & 7) * P.per_xcd + (id >> 3);
+  if (logical >= P.total) return;
+  const int rbk = logical % P.nrb, vb = logical / P.nrb;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int mt = wave & 3, kh = wave >> 2;
+  const int ln = lane & 31, lh = lane >> 5;
+  unsigned char* hid = lm_lds + kh * 2 * kLmHidBuf;
+  unsigned char* wst = lm_lds + kLmHidBytes + wave * 2 * kLmWBuf;
+  const int K2 = P.K >> 1;
+  const int nch = K2 / kLmKC;
+  const int kbase = kh * K2;
+  const int v0 = vb * kLmVB + mt * 32;
+  const int r0 = rbk * kLmRB;
+
+  // staging: 8 lanes cover the 128 bytes of one row slice
+  const int t = tid & 255;
+  const uint16_t* wsrc[4];
+  const uint16_t* hsrc[4];
+  int wdst[4], hdst[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int vrow = v0 + (lane >> 3) + 8 * j;
+    vrow = vrow < P.V ? vrow : P.V - 1;
+    wsrc[j] = P.weight + static_cast<int64_t>(vrow) * P.K + kbase + (lane & 7) * 8;
+    wdst[j] = ((lane >> 3) + 8 * j) * kLmPitch + (lane & 7) * 16;
+    int hrow = r0 + (t >> 3) + 32 * j;
+    hrow = hrow < P.rows ? hrow : P.rows - 1;
+    hsrc[j] = P.hidden + static_cast<int64_t>(hrow) * P.K + kbase + (t & 7) * 8;
+    hdst[j] = ((t >> 3) + 32 * j) * kLmPitch + (t & 7) * 16;
+  }
+  lm_u32x4 wreg[4], hreg[4];
+  auto load_slice = [&](int c) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      wreg[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
+      hreg[j] = *reinterpret_cast<const lm_u32x4*>(hsrc[j] + c * kLmKC);
+    }
+  };
+  auto store_slice = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      *reinterpret_cast<lm_u32x4*>(wst + buf * kLmWBuf + wdst[j]) = wreg[j];
+      *reinterpret_cast<lm_u32x4*>(hid + buf * kLmHidBuf + hdst[j]) = hreg[j];
+    }
+  };
+
+  lm_f32x16 acc[4];
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+
+  load_slice(0);
+  store_slice(0);
+  if (nch > 1) load_slice(1);
+  __syncthreads();
+  for (int c = 0; c < nch; ++c) {
+    const int buf = c & 1;
+    const unsigned char* wrd = wst + buf * kLmWBuf + ln * kLmPitch + lh * 16;
+    const unsigned char* hrd = hid + buf * kLmHidBuf + ln * kLmPitch + lh * 16;
+#pragma unroll
+    for (int s = 0; s < kLmKC / 16; ++s) {
+      const lm_bf16x8 a = __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(wrd + 32 * s));
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        const lm_bf16x8 b =
+            __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(hrd + nt * 32 * kLmPitch + 32 * s));
+        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+      }
+    }
+    if (c + 1 < nch) store_slice(buf ^ 1);
+    if (c + 2 < nch) load_slice(c + 2);
+    __syncthreads();
+  }
+
+  // add the two halves of the contraction: the upper half hands its tile over through LDS
+  float* red = reinterpret_cast<float*>(lm_lds);
+  if (kh == 1) {
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[((mt * 64 + nt * 16 + r) << 6) + lane] = acc[nt][r];
+  }
+  __syncthreads();
+  float2* sh_stat = reinterpret_cast<float2*>(lm_lds + kLmHidBytes);     // [4 tiles][128 rows]
+  if (kh == 0) {
+    const bool vec4 = (P.V & 3) == 0;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      const int row = r0 + nt * 32 + ln;
+      const bool row_ok = row < P.rows;
+      uint16_t* out = P.logits + static_cast<int64_t>(row_ok ? row : 0) * P.V;
+      float x[16];
+      float m = -INFINITY;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int vg = v0 + 8 * g + 4 * lh;
+        uint32_t b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = 4 * g + i;
+          b[i] = f32_to_bf16_rne(acc[nt][r] + red[((mt * 64 + nt * 16 + r) << 6) + lane]);
+          x[r] = (vg + i < P.V) ? __uint_as_float(b[i] << 16) : -INFINITY;
+          m = fmaxf(m, x[r]);
+        }
+        if (row_ok) {
+          if (vec4 && vg + 3 < P.V) {
+            lm_u32x2 w;
+            w.x = b[0] | (b[1] << 16);
+            w.y = b[2] | (b[3] << 16);
+            *reinterpret_cast<lm_u32x2*>(out + vg) = w;
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (vg + i < P.V) out[vg + i] = static_cast<uint16_t>(b[i]);
+          }
+        }
+      }
+      const float mm = (m == -INFINITY) ? 0.f : m;
+      float s = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += fast_exp2((x[r] - mm) * P.c);
+      // the other half-wave holds the same row's other 16 classes
+      const float mo = __shfl_xor(m, 32, kWave);
+      const float so = __shfl_xor(s, 32, kWave);
+      const float M = fmaxf(m, mo);
+      const float MM = (M == -INFINITY) ? 0.f : M;
+      const float mmo = (mo == -INFINITY) ? 0.f : mo;
+      const float S = s * fast_exp2((mm - MM) * P.c) + so * fast_exp2((mmo - MM) * P.c);
+      if (lh == 0) sh_stat[mt * kLmRB + nt * 32 + ln] = make_float2(M, S);
+    }
+  }
+  __syncthreads();
+  if (tid < kLmRB) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) M = fmaxf(M, sh_stat[i * kLmRB + tid].x);
+    const float MM = (M == -INFINITY) ? 0.f : M;
+    float S = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float2 st = sh_stat[i * kLmRB + tid];
+      const float mi = (st.x == -INFINITY) ? 0.f : st.x;
+      S += st.y * fast_exp2((mi - MM) * P.c);
+    }
+    const int row = r0 + tid;
+    if (row < P.rows) P.bstats[static_cast<int64_t>(row) * P.nvb + vb] = make_float2(M, S);
+  }
+}
+
+// One wave per (row, 8192-class segment): the 64 block statistics of the segment become the entry
+// the acceptance walk reads.
+__global__ __launch_bounds__(kWave) void lm_stats_merge_kernel(const float2* __restrict__ bstats, int nvb, int nseg,
+                                                               float c, SegStat* __restrict__ stats) {
+  const int seg = blockIdx.x, row = blockIdx.y, lane = threadIdx.x;
+  const int i = seg * kLmBlocksPerSeg + lane;
+  float m = -INFINITY, s = 0.f;
+  if (i < nvb) {
+    const float2 b = bstats[static_cast<int64_t>(row) * nvb + i];
+    m = b.x; s = b.y;
+  }
+  const float M = wave_max(m);
+  const float MM = (M == -INFINITY) ? 0.f : M;
+  const float mm = (m == -INFINITY) ? 0.f : m;
+  const double z = wave_sum(static_cast<double>(s) * static_cast<double>(fast_exp2((mm - MM) * c)));
+  if (lane == 0) {
+    SegStat st;
+    st.m = M; st.pad = 0.f; st.z = z;
+    stats[static_cast<int64_t>(row) * nseg + seg] = st;
+  }
+}
+
+size_t lm_head_workspace_bytes(int rows, int V) {
+  const size_t nvb = (static_cast<size_t>(V) + kLmVB - 1) / kLmVB;
+  return static_cast<size_t>(rows) * nvb * sizeof(float2) + 256;
+}
+
+size_t row_stats_bytes(int rows, int V) { return static_cast<size_t>(rows) * stats_segments(V) * sizeof(SegStat); }
+
+int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
+  if (a.rows <= 0) return 0;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kLmLds) != hipSuccess)
+      return -1;
+    attr_set = true;
+  }
+  LmParams P;
+  P.rows = a.rows; P.K = a.d_model; P.V = a.V;
+  P.nvb = (a.V + kLmVB - 1) / kLmVB;
+  P.nrb = (a.rows + kLmRB - 1) / kLmRB;
+  P.total = P.nvb * P.nrb;
+  P.per_xcd = (P.total + 7) / 8;
+  P.c = kLog2e / a.temperature;
+  P.hidden = static_cast<const uint16_t*>(a.hidden);
+  P.weight = static_cast<const uint16_t*>(a.weight);
+  P.logits = static_cast<uint16_t*>(a.logits);
+  P.bstats = static_cast<float2*>(a.workspace);
+  hipLaunchKernelGGL(lm_head_kernel, dim3(P.per_xcd * 8), dim3(kLmThreads), kLmLds, stream, P);
+  const int nseg = stats_segments(a.V);
+  hipLaunchKernelGGL(lm_stats_merge_kernel, dim3(nseg, a.rows), dim3(kWave), 0, stream, P.bstats, P.nvb, nseg, P.c,
+                     static_cast<SegStat*>(a.stats));
+  return 0;
+}
+
+}  // namespace specv

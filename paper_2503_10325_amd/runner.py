@@ -116,11 +116,50 @@ class DeviceAccept:
                        self.u_resample, self.accept_len, self.out_tokens, self.stop_node, self.dbg_ratio,
                        self.workspace, stream)
 
+    def run_prestats(self, stream=None):
+        """The workspace already starts with the target rows' statistics (DeviceLmHead wrote them)."""
+        sv.spec_accept_prestats(self.B, self.total, self.max_nodes, self.node_offsets, self.parent,
+                                self.draft_tokens, self.target, self.draft_q, self.q_kind, self.q_row,
+                                self.temperature, self.u_accept, self.u_resample, self.accept_len, self.out_tokens,
+                                self.stop_node, self.dbg_ratio, self.workspace, stream)
+
     def results(self):
         torch.cuda.synchronize()
         return dict(accept_len=self.accept_len.cpu().numpy(), out_tokens=self.out_tokens.cpu().numpy(),
                     stop_node=self.stop_node.cpu().numpy(),
                     ratio=None if self.dbg_ratio is None else self.dbg_ratio.cpu().numpy()[:self.total])
+
+
+class DeviceLmHead:
+    """LM-head inputs resident on the GPU, the logits it produces and the statistics buffer
+    (its own, or the head of an acceptance workspace handed in as ``stats``)."""
+
+    def __init__(self, li: W.LmHeadInputs, temperature=1.0, stats=None, device="cuda"):
+        self.hidden = bf16_to_device(li.hidden, device)
+        self.weight = bf16_to_device(li.weight, device)
+        self.rows, self.d_model = li.hidden.shape
+        self.V = li.weight.shape[0]
+        self.temperature = temperature
+        self.logits = torch.empty((self.rows, self.V), dtype=torch.bfloat16, device=device)
+        n = max(sv.spec_row_stats_size(self.rows, self.V), 16)
+        self.stats = torch.zeros(n, dtype=torch.uint8, device=device) if stats is None else stats
+        self.workspace = torch.empty(max(sv.spec_lm_head_workspace_size(self.rows, self.V), 256), dtype=torch.uint8,
+                                     device=device)
+
+    def run(self, stream=None):
+        sv.spec_lm_head(self.hidden, self.weight, self.temperature, self.logits, self.stats, self.workspace, stream)
+
+    def logits_bits(self):
+        torch.cuda.synchronize()
+        return self.logits.view(torch.int16).cpu().numpy().view(np.uint16)
+
+    def segment_stats(self):
+        """(m [rows, nseg] float32, z [rows, nseg] float64) as the acceptance walk reads them."""
+        torch.cuda.synchronize()
+        nseg = (self.V + 8191) // 8192
+        raw = self.stats[: self.rows * nseg * 16].cpu().numpy()
+        rec = raw.view(np.dtype([("m", "<f4"), ("pad", "<f4"), ("z", "<f8")])).reshape(self.rows, nseg)
+        return rec["m"].copy(), rec["z"].copy()
 
 
 class DeviceGreedy:

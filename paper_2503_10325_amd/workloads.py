@@ -365,6 +365,21 @@ def make_routing_inputs(batch: int, k_max: int, n_drafters: int, vocab: int, emb
     return RoutingInputs(k_len, conf, draft_tokens, accept_len, out_tokens, embedding)
 
 
+@dataclasses.dataclass
+class LmHeadInputs:
+    hidden: np.ndarray         # [rows, d_model] bf16 bits: final hidden states of the verified positions
+    weight: np.ndarray         # [vocab, d_model] bf16 bits: one row per vocabulary entry
+
+
+def make_lm_head_inputs(rows: int, d_model: int, vocab: int, seed: int = 0, logit_sd: float = 3.0) -> LmHeadInputs:
+    """Hidden states ~ N(0, 1) and weights ~ N(0, logit_sd / sqrt(d_model)): the logits then have the
+    spread (standard deviation logit_sd) of the acceptance workloads' target rows."""
+    name = f"lm_head_{rows}x{d_model}x{vocab}"
+    hidden = _normal_bf16(_rng(seed, name, "hidden"), (rows, d_model))
+    weight = _normal_bf16(_rng(seed, name, "weight"), (vocab, d_model), logit_sd / float(np.sqrt(d_model)))
+    return LmHeadInputs(hidden, weight)
+
+
 def attention_bytes_flops(cfg: VerifyConfig, st: DraftStructure) -> Tuple[int, int]:
     """Bytes the attention step must move (K and V of every cached position once per KV
     head, Q in, bf16 O out) and its floating-point operation count (QK^T and PV)."""

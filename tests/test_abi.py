@@ -115,3 +115,23 @@ def test_greedy_routing_adaptive_validation_needs_no_gpu():
     assert adaptive() == -1
     assert adaptive(R=-1) == -2
     assert adaptive(R=0) == 0
+
+
+def test_lm_head_validation_needs_no_gpu():
+    L = sv.lib()
+    null = ctypes.c_void_p(0)
+
+    def lm(rows=4, d=256, V=100, T=1.0):
+        return L.spec_lm_head(rows, d, V, null, null, T, null, null, null, 0, null)
+
+    assert lm() == -1
+    assert lm(d=0) == -2
+    assert lm(T=0.0) == -2
+    assert lm(d=200) == -3                      # contraction length must be a multiple of 128
+    assert lm(rows=70000) == -3
+    assert lm(rows=0) == 0
+    assert sv.spec_row_stats_size(4, 8192) == 4 * 16 and sv.spec_row_stats_size(4, 8193) == 4 * 2 * 16
+    assert sv.spec_lm_head_workspace_size(4, 100) >= 4 * 8
+    a = L.spec_accept_prestats(2, 100, 4, 4, 2, null, null, null, null, 1, null, 0, 0, null, 1.0,
+                               null, null, null, null, 3, null, null, null, 0, null)
+    assert a == -3                              # statistics from the LM head describe bf16 logits
