@@ -20,6 +20,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 METRIC = "verified draft tokens/sec + achieved HBM GB/s (verify-attn+accept), 1 MI355X"
 
 
@@ -46,6 +47,11 @@ def parse_args():
     ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
                     help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
                          "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
+    ap.add_argument("--lm-head", action="store_true",
+                    help="also run the projection that produces the target logits (spec_lm_head on synthetic "
+                         "[rows, d_model] hidden states and a [vocab, d_model] bf16 weight, d_model = heads x "
+                         "head_dim) inside the step; acceptance then starts from its statistics "
+                         "(spec_accept_prestats).  Not the headline step: the line gains an lm_head object")
     return ap.parse_args()
 
 
@@ -63,9 +69,10 @@ def read_traffic(workload):
 class Step:
     """Device state of one input copy and the three calls of one step."""
 
-    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto", routing=False):
+    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto", routing=False, lm=None):
         import torch
         self.routing = None
+        self.head = None
         self.attn = runner.DeviceAttn(a, want_lse=False)
         st = a.st
         if ai.fusion is not None:
@@ -112,9 +119,20 @@ class Step:
         if accept_mode == "greedy":
             # same target rows and draft tokens, no draft distributions or uniforms
             self.accept = runner.DeviceGreedy(st, self.accept.target, self.accept.draft_tokens)
+        if lm is not None:
+            # the target rows come from the projection (written into the tensor the acceptance step
+            # reads), their statistics go to the head of the acceptance workspace
+            sampling = accept_mode == "sampling"
+            self.head = runner.DeviceLmHead(lm, temperature=cfg.temperature,
+                                            stats=self.accept.workspace if sampling else None)
+            self.head.logits = self.accept.target
+            if sampling:
+                self.accept.run = self.accept.run_prestats
 
     def run(self):
         self.attn.run()
+        if self.head is not None:
+            self.head.run()
         if self.fuse is not None:
             self.fuse.run()
         self.accept.run()
@@ -122,11 +140,20 @@ class Step:
             self.routing()
 
 
-def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling"):
+def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None):
     """The oracle, as it stands, timed on the host cores over whole batches of the workload."""
     import oracle
     reps, t_total = 0, 0.0
     tokens = int(a.st.total)
+    lm_note, lm_s = "", 0.0
+    if lm is not None:
+        # the projection is timed once on a few rows and scaled to all of them (it is linear in rows)
+        rows = lm.hidden.shape[0]
+        r = min(rows, 4)
+        t0 = time.perf_counter()
+        oracle.lm_head(lm.hidden[:r], lm.weight, temperature=cfg.temperature)
+        lm_s = (time.perf_counter() - t0) * rows / r
+        lm_note = f"; plus the projection, timed on {r} of {rows} rows and scaled: {lm_s:.2f} s per pass"
     while reps < 1 or (t_total < budget_s and reps < 50):
         t0 = time.perf_counter()
         oracle.verify_attn(a.q, a.k_pool, a.v_pool, a.block_table, a.st.ctx_len, a.st.node_offsets,
@@ -143,9 +170,10 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling"):
                           ai.u_resample, temperature=cfg.temperature)
         t_total += time.perf_counter() - t0
         reps += 1
-    return dict(value=tokens * reps / t_total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+    return dict(value=tokens * reps / (t_total + reps * lm_s), unit="tokens/s", cores=oracle.num_threads(),
+                kind="oracle",
                 sample=f"{reps} pass(es) over the full {cfg.name} batch ({tokens} draft tokens each), "
-                       f"{t_total:.2f} s of oracle time")
+                       f"{t_total:.2f} s of oracle time" + lm_note)
 
 
 def main():
@@ -163,8 +191,22 @@ def main():
         sys.exit(2)
     cfg = W.CONFIGS[args.workload]
     a = W.make_attn_inputs(cfg, seed=args.seed)
-    ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
-    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse, args.routing) for _ in range(max(1, args.copies))]
+    lm = None
+    if args.lm_head:
+        # Target rows = the projection of synthetic hidden states, evaluated here on the host (fp32
+        # accumulation, rounded to bf16) so that drafts and the CPU baseline see logits that do not come
+        # from the GPU; the GPU recomputes them every step.
+        rows = int(a.st.total) + cfg.batch
+        lm = W.make_lm_head_inputs(rows, cfg.d_model, cfg.vocab, seed=args.seed, logit_sd=cfg.target_sd)
+        hf = torch.from_numpy(W.bf16_bits_to_f32(lm.hidden))
+        wf = torch.from_numpy(W.bf16_bits_to_f32(lm.weight))
+        host_logits = (hf @ wf.t()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        del hf, wf
+        ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st, target_logits=host_logits)
+    else:
+        ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
+    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse, args.routing, lm)
+              for _ in range(max(1, args.copies))]
     torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -212,6 +254,28 @@ def main():
     torch.cuda.synchronize()
     attn_ms = np.array([e0.elapsed_time(e1) for e0, e1 in ev])
     attn_s = float(attn_ms.mean()) * 1e-3
+    lm_obj = None
+    if lm is not None:
+        for i in range(n_ev):
+            c = copies[i % len(copies)]
+            ev[i][0].record()
+            c.head.run()
+            ev[i][1].record()
+        torch.cuda.synchronize()
+        lm_s = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e-3
+        rows = lm.hidden.shape[0]
+        w_bytes = cfg.vocab * cfg.d_model * 2
+        lm_bytes = w_bytes + rows * cfg.d_model * 2 + rows * cfg.vocab * 2       # weight + hidden read, logits written
+        lm_flops = 2.0 * rows * cfg.d_model * cfg.vocab
+        mfma_time, hbm_time = lm_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12), lm_bytes / (HBM_PEAK_GBS * 1e9)
+        bound = "hbm" if hbm_time >= mfma_time else "mfma"
+        ach = lm_bytes / lm_s / 1e9 if bound == "hbm" else lm_flops / lm_s / 1e12
+        peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS
+        lm_obj = {"kernel": "spec_lm_head: lm_head_kernel + lm_stats_merge_kernel (duration is the whole call)",
+                  "rows": rows, "d_model": cfg.d_model, "vocab": cfg.vocab, "launch_us_mean": lm_s * 1e6,
+                  "roofline": {"bound": bound, "achieved": ach, "peak": peak,
+                               "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak,
+                               "algorithmic_bytes": lm_bytes, "flops": lm_flops}}
     if args.calibration_copy_mb > 0:
         # a plain copy kernel of known size: reads N MiB and writes N MiB
         src = torch.empty(args.calibration_copy_mb << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -253,8 +317,10 @@ def main():
         "data": "synthetic",
         "launch_mode": "eager" if graphs is None else "hip_graph_replay",
         "accept_mode": args.accept_mode,
-        "calls_per_step": ["spec_verify_attn"] + (["spec_fuse_drafts"] if copies[0].fuse is not None else []) +
-                          ["spec_accept" if args.accept_mode == "sampling" else "spec_accept_greedy"] +
+        "calls_per_step": ["spec_verify_attn"] + (["spec_lm_head"] if lm is not None else []) +
+                          (["spec_fuse_drafts"] if copies[0].fuse is not None else []) +
+                          [("spec_accept_prestats" if lm is not None else "spec_accept")
+                           if args.accept_mode == "sampling" else "spec_accept_greedy"] +
                           (["spec_routing_scores"] if copies[0].routing is not None else []),
         "config": {"workload": cfg.name, "batch": cfg.batch, "draft_tokens_per_step": tokens,
                    "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
@@ -268,8 +334,10 @@ def main():
                      "launch_us_p90": float(np.percentile(attn_ms, 90)) * 1e3,
                      "mfma_tflops": attn_flops / attn_s / 1e12},
     }
+    if lm_obj is not None:
+        out["lm_head"] = lm_obj
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds, args.accept_mode)
+        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds, args.accept_mode, lm)
     print(json.dumps(out))
 
 

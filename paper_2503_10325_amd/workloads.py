@@ -73,6 +73,11 @@ class VerifyConfig:
     def group(self) -> int:
         return self.n_q_heads // self.n_kv_heads
 
+    @property
+    def d_model(self) -> int:
+        """Width of the hidden state the LM head contracts over (heads x head_dim in the Llama family)."""
+        return self.n_q_heads * self.head_dim
+
 
 CONFIGS = {
     "c0_tiny": VerifyConfig("c0_tiny", 1, 8, 8, 64, ("fixed", 256), ("linear", 4),
@@ -267,7 +272,7 @@ def _gumbel_argmax(r: np.random.Generator, logits_bits_row: np.ndarray, inv_t: f
 
 
 def make_accept_inputs(cfg: VerifyConfig, seed: int = 0, st: Optional[DraftStructure] = None,
-                       draft_equals_target: bool = False) -> AcceptInputs:
+                       draft_equals_target: bool = False, target_logits: Optional[np.ndarray] = None) -> AcceptInputs:
     """Target logits ~ N(0, target_sd) per row; draft rows per ``cfg.q_src``; draft
     tokens are samples of the very draft rows handed to the acceptance step (siblings
     of a tree are i.i.d. draws from their parent's row and share ``q_row``)."""
@@ -275,7 +280,11 @@ def make_accept_inputs(cfg: VerifyConfig, seed: int = 0, st: Optional[DraftStruc
     B, V = cfg.batch, cfg.vocab
     total = st.total
     inv_t = 1.0 / cfg.temperature
-    tgt = _normal_bf16(_rng(seed, cfg.name, "target_logits"), (total + B, V), cfg.target_sd)
+    if target_logits is None:
+        tgt = _normal_bf16(_rng(seed, cfg.name, "target_logits"), (total + B, V), cfg.target_sd)
+    else:                                   # rows given by the caller (bf16 bits), e.g. an LM-head product
+        tgt = np.ascontiguousarray(target_logits, dtype=np.uint16)
+        assert tgt.shape == (total + B, V)
     r_tok = _rng(seed, cfg.name, "draft_tokens")
     r_noise = _rng(seed, cfg.name, "draft_noise")
     u_acc = uniforms24(_rng(seed, cfg.name, "u_accept"), total)
