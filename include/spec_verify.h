@@ -303,7 +303,7 @@ int32_t spec_compact_kv(
  * 65535; up to 128 rows the weight matrix is read once.
  * ---------------------------------------------------------------------------- */
 size_t spec_row_stats_size(int32_t rows, int32_t V);
-size_t spec_lm_head_workspace_size(int32_t rows, int32_t V);
+size_t spec_lm_head_workspace_size(int32_t rows, int32_t d_model, int32_t V);
 
 int32_t spec_lm_head(
     int32_t rows, int32_t d_model, int32_t V,

@@ -86,7 +86,7 @@ def lib() -> ctypes.CDLL:
         L.spec_row_stats_size.restype = sz
         L.spec_row_stats_size.argtypes = [i32, i32]
         L.spec_lm_head_workspace_size.restype = sz
-        L.spec_lm_head_workspace_size.argtypes = [i32, i32]
+        L.spec_lm_head_workspace_size.argtypes = [i32, i32, i32]
         L.spec_lm_head.restype = i32
         L.spec_lm_head.argtypes = [i32, i32, i32, vp, vp, f32, vp, vp, vp, sz, vp]
         _lib = L
@@ -207,8 +207,8 @@ def spec_row_stats_size(rows, V) -> int:
     return int(lib().spec_row_stats_size(rows, V))
 
 
-def spec_lm_head_workspace_size(rows, V) -> int:
-    return int(lib().spec_lm_head_workspace_size(rows, V))
+def spec_lm_head_workspace_size(rows, d_model, V) -> int:
+    return int(lib().spec_lm_head_workspace_size(rows, d_model, V))
 
 
 def spec_lm_head(hidden, weight, temperature, logits, target_stats, workspace, stream=None) -> None:

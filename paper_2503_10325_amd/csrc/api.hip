@@ -170,9 +170,9 @@ size_t spec_row_stats_size(int32_t rows, int32_t V) {
   return row_stats_bytes(rows, V);
 }
 
-size_t spec_lm_head_workspace_size(int32_t rows, int32_t V) {
-  if (rows < 0 || V <= 0) return 0;
-  return lm_head_workspace_bytes(rows, V);
+size_t spec_lm_head_workspace_size(int32_t rows, int32_t d_model, int32_t V) {
+  if (rows < 0 || d_model <= 0 || V <= 0) return 0;
+  return lm_head_workspace_bytes(rows, d_model, V);
 }
 
 int32_t spec_lm_head(int32_t rows, int32_t d_model, int32_t V, const void* hidden, const void* weight,
@@ -186,7 +186,7 @@ int32_t spec_lm_head(int32_t rows, int32_t d_model, int32_t V, const void* hidde
   if ((reinterpret_cast<uintptr_t>(hidden) | reinterpret_cast<uintptr_t>(weight)) & 15u) return SPEC_ERR_SHAPE;
   if ((reinterpret_cast<uintptr_t>(logits) & 7u) || (reinterpret_cast<uintptr_t>(target_stats) & 15u))
     return SPEC_ERR_SHAPE;
-  if (!workspace || workspace_bytes < lm_head_workspace_bytes(rows, V)) return SPEC_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < lm_head_workspace_bytes(rows, d_model, V)) return SPEC_ERR_WORKSPACE;
   LmHeadArgs a{};
   a.rows = rows; a.d_model = d_model; a.V = V; a.hidden = hidden; a.weight = weight; a.temperature = temperature;
   a.logits = logits; a.stats = target_stats; a.workspace = workspace;

@@ -46,7 +46,7 @@ struct LmHeadArgs {
   void* stats;
   void* workspace;
 };
-size_t lm_head_workspace_bytes(int rows, int V);
+size_t lm_head_workspace_bytes(int rows, int d_model, int V);
 size_t row_stats_bytes(int rows, int V);
 int launch_lm_head(const LmHeadArgs& a, hipStream_t stream);
 

@@ -18,6 +18,8 @@
 // (rows padded to 144 bytes: conflict-free 16-byte operand reads), one slice ahead, one barrier per
 // slice.  Weight slices are private to their wave; hidden slices are shared by the four waves of a
 // half.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -212,6 +214,184 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
   }
 }
 
+// ----------------------------------------------------------------------------------
+// More than 128 rows: the product is bound by the matrix cores, and what limits them is operand
+// delivery.  Each wave owns a [128 vocab x 64 rows] tile (8 accumulator tiles); the four waves of a
+// workgroup share one 128-entry weight slice in LDS (each weight operand read feeds two matrix
+// instructions) and cover 256 rows.  The hidden operands never touch LDS: a small pre-pass re-lays
+// the hidden states out in the order the matrix instruction reads them, so that one load
+// instruction fetches 1 KB of contiguous memory (8 cache lines instead of 64 for a row-major
+// operand, whose lanes walk down 32 different rows - the L1 tag rate, one line per clock, is what
+// bounds such loads).  Inside a 64-wide slice the contraction index is permuted (lane half h, step
+// j, element i  <->  k = 32 h + 8 j + i) in both operands alike.
+//
+// Packed hidden states: [row tile of 32][slice][step j = 0..3][lane 0..63] x 16 bytes,
+// lane L holding hidden[32 tile + L % 32][64 slice + 32 (L / 32) + 8 j .. + 8]; rows past the end
+// are zero.
+// ----------------------------------------------------------------------------------
+constexpr int kLwThreads = 256;
+constexpr int kLwRB = 256;                          // hidden rows per workgroup (4 waves x 64)
+constexpr int kLwLds = 2 * kLmHidBuf;               // two weight slices of 128 entries
+
+__global__ __launch_bounds__(256) void lm_pack_hidden_kernel(const uint16_t* __restrict__ hidden, int rows, int K,
+                                                             int64_t n_items, lm_u32x4* __restrict__ packed) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= n_items) return;
+  const int nch = K / kLmKC;
+  const int L = static_cast<int>(idx & 63);
+  const int j = static_cast<int>((idx >> 6) & 3);
+  const int64_t blk = idx >> 8;                      // tile * nch + slice
+  const int c = static_cast<int>(blk % nch);
+  const int64_t row = (blk / nch) * 32 + (L & 31);
+  lm_u32x4 v = {0u, 0u, 0u, 0u};
+  if (row < rows) v = *reinterpret_cast<const lm_u32x4*>(hidden + row * K + c * kLmKC + 32 * (L >> 5) + 8 * j);
+  packed[idx] = v;
+}
+
+__global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P, const lm_u32x4* __restrict__ packed) {
+  extern __shared__ __align__(16) unsigned char lm_lds[];
+  const int id = blockIdx.x;
+  const int logical = (id & 7) * P.per_xcd + (id >> 3);
+  if (logical >= P.total) return;
+  const int rbk = logical % P.nrb, vb = logical / P.nrb;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int v0 = vb * kLmVB;
+  const int r0 = rbk * kLwRB + wave * 64;             // this wave's first row
+  const int left = P.rows - r0;
+  const int ntc = left >= 64 ? 2 : (left <= 0 ? 0 : (left + 31) >> 5);      // row tiles of this wave that hold rows
+  const int nch = P.K / kLmKC;
+
+  // weight slice: 128 entries x 128 bytes, 8 lanes per row
+  const uint16_t* wsrc[4];
+  int wdst[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int vrow = v0 + (tid >> 3) + 32 * j;
+    vrow = vrow < P.V ? vrow : P.V - 1;
+    wsrc[j] = P.weight + static_cast<int64_t>(vrow) * P.K + (tid & 7) * 8;
+    wdst[j] = ((tid >> 3) + 32 * j) * kLmPitch + (tid & 7) * 16;
+  }
+  // packed hidden operands of this wave's two row tiles (a wave without rows reads tile 0)
+  const int tile0 = ntc > 0 ? (r0 >> 5) : 0;
+  const lm_u32x4* hsrc[2];
+  hsrc[0] = packed + static_cast<int64_t>(tile0) * nch * 256 + lane;
+  hsrc[1] = packed + static_cast<int64_t>(ntc > 1 ? tile0 + 1 : tile0) * nch * 256 + lane;
+
+  lm_u32x4 wreg[4];
+  auto load_weight = [&](int c) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wreg[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
+  };
+  auto store_weight = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<lm_u32x4*>(lm_lds + buf * kLmHidBuf + wdst[j]) = wreg[j];
+  };
+  auto load_hidden = [&](int c, lm_u32x4 (&b)[2][4]) {
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[ni][j] = hsrc[ni][(c * 4 + j) * 64];
+  };
+
+  lm_f32x16 acc[4][2];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  auto compute = [&](int buf, const lm_u32x4 (&b)[2][4]) {
+    if (ntc == 0) return;
+    const unsigned char* wrd = lm_lds + buf * kLmHidBuf + ln * kLmPitch + lh * 64;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+        const lm_bf16x8 a =
+            __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch + 16 * j));
+        acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(lm_bf16x8, b[0][j]), acc[mi][0], 0, 0, 0);
+        if (ntc > 1)
+          acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(lm_bf16x8, b[1][j]), acc[mi][1], 0, 0, 0);
+      }
+    }
+  };
+
+  lm_u32x4 b0[2][4], b1[2][4];
+  load_weight(0);
+  load_hidden(0, b0);
+  store_weight(0);
+  if (nch > 1) load_weight(1);
+  __syncthreads();
+  // two slices per trip so that the two hidden register sets keep their names
+  for (int c = 0; c < nch; c += 2) {
+    if (c + 1 < nch) load_hidden(c + 1, b1);
+    compute(0, b0);
+    if (c + 1 < nch) store_weight(1);
+    if (c + 2 < nch) load_weight(c + 2);
+    __syncthreads();
+    if (c + 1 < nch) {
+      if (c + 2 < nch) load_hidden(c + 2, b0);
+      compute(1, b1);
+      if (c + 2 < nch) store_weight(0);
+      if (c + 3 < nch) load_weight(c + 3);
+      __syncthreads();
+    }
+  }
+
+  // each wave holds all 128 vocabulary entries of the block for its rows: statistics need no LDS
+  const bool vec4 = (P.V & 3) == 0;
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni) {
+    const int row = r0 + ni * 32 + ln;
+    const bool row_ok = row < P.rows;
+    uint16_t* out = P.logits + static_cast<int64_t>(row_ok ? row : 0) * P.V;
+    float m = -INFINITY;
+    float x[4][16];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int vg = v0 + 32 * mi + 8 * g + 4 * lh;
+        uint32_t b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = 4 * g + i;
+          b[i] = f32_to_bf16_rne(acc[mi][ni][r]);
+          x[mi][r] = (vg + i < P.V) ? __uint_as_float(b[i] << 16) : -INFINITY;
+          m = fmaxf(m, x[mi][r]);
+        }
+        if (row_ok) {
+          if (vec4 && vg + 3 < P.V) {
+            lm_u32x2 w;
+            w.x = b[0] | (b[1] << 16);
+            w.y = b[2] | (b[3] << 16);
+            *reinterpret_cast<lm_u32x2*>(out + vg) = w;
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (vg + i < P.V) out[vg + i] = static_cast<uint16_t>(b[i]);
+          }
+        }
+      }
+    }
+    const float mm = (m == -INFINITY) ? 0.f : m;
+    float s = 0.f;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += fast_exp2((x[mi][r] - mm) * P.c);
+    const float mo = __shfl_xor(m, 32, kWave);
+    const float so = __shfl_xor(s, 32, kWave);
+    const float M = fmaxf(m, mo);
+    const float MM = (M == -INFINITY) ? 0.f : M;
+    const float mmo = (mo == -INFINITY) ? 0.f : mo;
+    const float S = s * fast_exp2((mm - MM) * P.c) + so * fast_exp2((mmo - MM) * P.c);
+    if (lh == 0 && row_ok) P.bstats[static_cast<int64_t>(row) * P.nvb + vb] = make_float2(M, S);
+  }
+}
+
 // One wave per (row, 8192-class segment): the 64 block statistics of the segment become the entry
 // the acceptance walk reads.
 __global__ __launch_bounds__(kWave) void lm_stats_merge_kernel(const float2* __restrict__ bstats, int nvb, int nseg,
@@ -234,9 +414,16 @@ __global__ __launch_bounds__(kWave) void lm_stats_merge_kernel(const float2* __r
   }
 }
 
-size_t lm_head_workspace_bytes(int rows, int V) {
+// Workspace: [block statistics rows x ceil(V/128) x 8 bytes][packed hidden states, more than 128 rows only]
+static size_t lm_bstats_bytes(int rows, int V) {
   const size_t nvb = (static_cast<size_t>(V) + kLmVB - 1) / kLmVB;
-  return static_cast<size_t>(rows) * nvb * sizeof(float2) + 256;
+  return (static_cast<size_t>(rows) * nvb * sizeof(float2) + 255) / 256 * 256;
+}
+
+size_t lm_head_workspace_bytes(int rows, int d_model, int V) {
+  size_t n = lm_bstats_bytes(rows, V) + 256;
+  if (rows > kLmRB) n += static_cast<size_t>((rows + 31) / 32) * 32 * d_model * sizeof(uint16_t);
+  return n;
 }
 
 size_t row_stats_bytes(int rows, int V) { return static_cast<size_t>(rows) * stats_segments(V) * sizeof(SegStat); }
@@ -250,10 +437,11 @@ int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
       return -1;
     attr_set = true;
   }
+  const bool wide = a.rows > kLmRB;
   LmParams P;
   P.rows = a.rows; P.K = a.d_model; P.V = a.V;
   P.nvb = (a.V + kLmVB - 1) / kLmVB;
-  P.nrb = (a.rows + kLmRB - 1) / kLmRB;
+  P.nrb = (a.rows + (wide ? kLwRB : kLmRB) - 1) / (wide ? kLwRB : kLmRB);
   P.total = P.nvb * P.nrb;
   P.per_xcd = (P.total + 7) / 8;
   P.c = kLog2e / a.temperature;
@@ -261,7 +449,15 @@ int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
   P.weight = static_cast<const uint16_t*>(a.weight);
   P.logits = static_cast<uint16_t*>(a.logits);
   P.bstats = static_cast<float2*>(a.workspace);
-  hipLaunchKernelGGL(lm_head_kernel, dim3(P.per_xcd * 8), dim3(kLmThreads), kLmLds, stream, P);
+  if (wide) {
+    lm_u32x4* packed = reinterpret_cast<lm_u32x4*>(static_cast<unsigned char*>(a.workspace) + lm_bstats_bytes(a.rows, a.V));
+    const int64_t n_items = static_cast<int64_t>((a.rows + 31) / 32) * (a.d_model / kLmKC) * 256;
+    hipLaunchKernelGGL(lm_pack_hidden_kernel, dim3(static_cast<unsigned>((n_items + 255) / 256)), dim3(256), 0, stream,
+                       P.hidden, a.rows, a.d_model, n_items, packed);
+    hipLaunchKernelGGL(lm_head_wide_kernel, dim3(P.per_xcd * 8), dim3(kLwThreads), kLwLds, stream, P, packed);
+  } else {
+    hipLaunchKernelGGL(lm_head_kernel, dim3(P.per_xcd * 8), dim3(kLmThreads), kLmLds, stream, P);
+  }
   const int nseg = stats_segments(a.V);
   hipLaunchKernelGGL(lm_stats_merge_kernel, dim3(nseg, a.rows), dim3(kWave), 0, stream, P.bstats, P.nvb, nseg, P.c,
                      static_cast<SegStat*>(a.stats));

@@ -143,7 +143,7 @@ class DeviceLmHead:
         self.logits = torch.empty((self.rows, self.V), dtype=torch.bfloat16, device=device)
         n = max(sv.spec_row_stats_size(self.rows, self.V), 16)
         self.stats = torch.zeros(n, dtype=torch.uint8, device=device) if stats is None else stats
-        self.workspace = torch.empty(max(sv.spec_lm_head_workspace_size(self.rows, self.V), 256), dtype=torch.uint8,
+        self.workspace = torch.empty(max(sv.spec_lm_head_workspace_size(self.rows, self.d_model, self.V), 256), dtype=torch.uint8,
                                      device=device)
 
     def run(self, stream=None):

@@ -131,7 +131,8 @@ def test_lm_head_validation_needs_no_gpu():
     assert lm(rows=70000) == -3
     assert lm(rows=0) == 0
     assert sv.spec_row_stats_size(4, 8192) == 4 * 16 and sv.spec_row_stats_size(4, 8193) == 4 * 2 * 16
-    assert sv.spec_lm_head_workspace_size(4, 100) >= 4 * 8
+    assert sv.spec_lm_head_workspace_size(4, 256, 100) >= 4 * 8
+    assert sv.spec_lm_head_workspace_size(200, 256, 100) >= 200 * 8 + 224 * 256 * 2      # packed hidden states
     a = L.spec_accept_prestats(2, 100, 4, 4, 2, null, null, null, null, 1, null, 0, 0, null, 1.0,
                                null, null, null, null, 3, null, null, null, 0, null)
     assert a == -3                              # statistics from the LM head describe bf16 logits

@@ -71,7 +71,8 @@ def check_lm_head(rt, rows, d_model, V, T, seed=0):
 @pytest.mark.parametrize("rows,d_model,V,T", [
     (70, 256, 3000, 1.0),        # ragged row tile, ragged vocabulary block
     (5, 128, 1001, 1.0),         # one slice per half, odd vocabulary (scalar stores)
-    (200, 512, 8300, 0.7),       # two row blocks, two statistics segments
+    (200, 512, 8300, 0.7),       # more than 128 rows: packed hidden states, last wave with one row tile
+    (300, 256, 1500, 1.0),       # two row blocks of 256, the second with 44 rows (three waves without rows)
     (128, 1024, 16384, 1.3),     # full tiles everywhere
     (1, 128, 130, 1.0),          # a single row, a second vocabulary block of two entries
 ])
