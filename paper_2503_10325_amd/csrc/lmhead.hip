@@ -20,6 +20,8 @@
 // half.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -259,7 +261,8 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
   const int v0 = vb * kLmVB;
   const int r0 = rbk * kLwRB + wave * 64;             // this wave's first row
   const int left = P.rows - r0;
-  const int ntc = left >= 64 ? 2 : (left <= 0 ? 0 : (left + 31) >> 5);      // row tiles of this wave that hold rows
+  // row tiles of this wave that hold rows; in a scalar register, so that the branches on it are scalar
+  const int ntc = __builtin_amdgcn_readfirstlane(left >= 64 ? 2 : (left <= 0 ? 0 : (left + 31) >> 5));
   const int nch = P.K / kLmKC;
 
   // weight slice: 128 entries x 128 bytes, 8 lanes per row
@@ -278,22 +281,6 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
   hsrc[0] = packed + static_cast<int64_t>(tile0) * nch * 256 + lane;
   hsrc[1] = packed + static_cast<int64_t>(ntc > 1 ? tile0 + 1 : tile0) * nch * 256 + lane;
 
-  lm_u32x4 wreg[4];
-  auto load_weight = [&](int c) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) wreg[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
-  };
-  auto store_weight = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) *reinterpret_cast<lm_u32x4*>(lm_lds + buf * kLmHidBuf + wdst[j]) = wreg[j];
-  };
-  auto load_hidden = [&](int c, lm_u32x4 (&b)[2][4]) {
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[ni][j] = hsrc[ni][(c * 4 + j) * 64];
-  };
-
   lm_f32x16 acc[4][2];
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
@@ -302,43 +289,90 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-  auto compute = [&](int buf, const lm_u32x4 (&b)[2][4]) {
-    if (ntc == 0) return;
-    const unsigned char* wrd = lm_lds + buf * kLmHidBuf + ln * kLmPitch + lh * 64;
+  // The whole slice loop exists three times - two, one or no row tile in this wave - and one scalar
+  // branch picks the copy: branches inside the loop would split the accumulators' live ranges.
+  // Every copy passes the same barriers.
+  auto slice_loop = [&](auto n_tiles) {
+    constexpr int NT = decltype(n_tiles)::value;
+    // Weight slices are fetched PF slices ahead into a ring of PF - 1 register sets.  A wave with two
+    // row tiles has registers for one set and enough matrix work per slice to cover the load; waves
+    // with less work (the last row block) would otherwise sit out a full load latency per slice.
+    constexpr int PF = NT == 2 ? 2 : 4;
+    constexpr int R = PF - 1;
+    lm_u32x4 wring[R][4];
+    auto load_weight = [&](int c, lm_u32x4 (&w)[4]) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < 4; ++j) w[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
+    };
+    auto store_weight = [&](int buf, const lm_u32x4 (&w)[4]) {
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi) {
-        const lm_bf16x8 a =
-            __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch + 16 * j));
-        acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(lm_bf16x8, b[0][j]), acc[mi][0], 0, 0, 0);
-        if (ntc > 1)
-          acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(lm_bf16x8, b[1][j]), acc[mi][1], 0, 0, 0);
+      for (int j = 0; j < 4; ++j) *reinterpret_cast<lm_u32x4*>(lm_lds + buf * kLmHidBuf + wdst[j]) = w[j];
+    };
+    const int last = nch - 1;
+    lm_u32x4 b[2][4];
+    {
+      lm_u32x4 w0[4];
+      load_weight(0, w0);
+      if constexpr (NT > 0) {
+        // same order as in the loop (step by step), so that the loop's wait counts stay tight
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int ni = 0; ni < NT; ++ni) b[ni][j] = hsrc[ni][j * 64];
+      }
+      store_weight(0, w0);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) load_weight(1 + r < last ? 1 + r : last, wring[r]);
+    __syncthreads();
+    // Loads and stores for the slices ahead are issued unconditionally (past the end they repeat the
+    // last slice and are never used): a branch around a load would make every wait count after it
+    // pessimistic.  The ring slot of a slice is static: R slices per trip.
+    for (int c0 = 0; c0 < nch; c0 += R) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int c = c0 + r;
+        if (c < nch) {
+          const int buf = c & 1;
+          const int c1 = c < last ? c + 1 : last;
+          const int cp = c + PF < last ? c + PF : last;
+          if constexpr (NT > 0) {
+            const unsigned char* wrd = lm_lds + buf * kLmHidBuf + ln * kLmPitch + lh * 64;
+            // weight operands are read one step ahead; a step's hidden operands are dead after its
+            // matrix instructions and are reloaded at once with the next slice's
+            lm_u32x4 a[2][4];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) a[0][mi] = *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              if (j < 3) {
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+                  a[(j + 1) & 1][mi] = *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch + 16 * (j + 1));
+              }
+#pragma unroll
+              for (int mi = 0; mi < 4; ++mi) {
+                acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][mi]),
+                                                                     __builtin_bit_cast(lm_bf16x8, b[0][j]), acc[mi][0], 0, 0, 0);
+                if constexpr (NT > 1)
+                  acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][mi]),
+                                                                       __builtin_bit_cast(lm_bf16x8, b[1][j]), acc[mi][1], 0, 0, 0);
+              }
+#pragma unroll
+              for (int ni = 0; ni < NT; ++ni) b[ni][j] = hsrc[ni][(c1 * 4 + j) * 64];
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+          store_weight(buf ^ 1, wring[r]);      // slice c + 1
+          load_weight(cp, wring[r]);            // slice c + PF takes its place
+          __syncthreads();
+        }
       }
     }
   };
-
-  lm_u32x4 b0[2][4], b1[2][4];
-  load_weight(0);
-  load_hidden(0, b0);
-  store_weight(0);
-  if (nch > 1) load_weight(1);
-  __syncthreads();
-  // two slices per trip so that the two hidden register sets keep their names
-  for (int c = 0; c < nch; c += 2) {
-    if (c + 1 < nch) load_hidden(c + 1, b1);
-    compute(0, b0);
-    if (c + 1 < nch) store_weight(1);
-    if (c + 2 < nch) load_weight(c + 2);
-    __syncthreads();
-    if (c + 1 < nch) {
-      if (c + 2 < nch) load_hidden(c + 2, b0);
-      compute(1, b1);
-      if (c + 2 < nch) store_weight(0);
-      if (c + 3 < nch) load_weight(c + 3);
-      __syncthreads();
-    }
-  }
+  if (ntc == 2) slice_loop(std::integral_constant<int, 2>{});
+  else if (ntc == 1) slice_loop(std::integral_constant<int, 1>{});
+  else slice_loop(std::integral_constant<int, 0>{});
 
   // each wave holds all 128 vocabulary entries of the block for its rows: statistics need no LDS
   const bool vec4 = (P.V & 3) == 0;
