@@ -11,8 +11,8 @@
 // transpose is needed anywhere.  One workgroup = 8 waves = 4 vocabulary tiles x 2 halves of the
 // contraction, producing a [128 vocab x 128 rows] block; the two halves are added through LDS.
 // With up to 128 rows (a verification batch) the weight matrix is read exactly once and the kernel
-// is bound by that read; more rows take further row blocks, which are scheduled next to each other
-// on one XCD so that the weight tile is served by that XCD's L2.
+// is bound by that read.  More rows go to a second kernel (below) whose row blocks are scheduled
+// next to each other on one XCD so that a weight tile is served by that XCD's L2.
 //
 // Both operands are staged global -> registers -> LDS in 64-wide slices of the contraction
 // (rows padded to 144 bytes: conflict-free 16-byte operand reads), one slice ahead, one barrier per
@@ -218,9 +218,10 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
 
 // ----------------------------------------------------------------------------------
 // More than 128 rows: the product is bound by the matrix cores, and what limits them is operand
-// delivery.  Each wave owns a [128 vocab x 64 rows] tile (8 accumulator tiles); the four waves of a
-// workgroup share one 128-entry weight slice in LDS (each weight operand read feeds two matrix
-// instructions) and cover 256 rows.  The hidden operands never touch LDS: a small pre-pass re-lays
+// delivery.  Each wave owns a [128 vocab x 64 rows] tile (8 accumulator tiles); the eight waves of a
+// workgroup (two per SIMD, one workgroup per CU) share one 128-entry weight slice in LDS (each
+// weight operand read feeds two matrix instructions) and cover 512 rows, so the slice is fetched and
+// staged once per 512 rows.  The hidden operands never touch LDS: a small pre-pass re-lays
 // the hidden states out in the order the matrix instruction reads them, so that one load
 // instruction fetches 1 KB of contiguous memory (8 cache lines instead of 64 for a row-major
 // operand, whose lanes walk down 32 different rows - the L1 tag rate, one line per clock, is what
@@ -230,9 +231,16 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
 // Packed hidden states: [row tile of 32][slice][step j = 0..3][lane 0..63] x 16 bytes,
 // lane L holding hidden[32 tile + L % 32][64 slice + 32 (L / 32) + 8 j .. + 8]; rows past the end
 // are zero.
+//
+// A last row block with few rows costs more than its rows: its workgroups run ahead of their
+// siblings and stream the weight matrix from HBM once more (they overlap with the matrix-bound full
+// blocks, but the row count at which the product is cheapest per row is a multiple of 512).
 // ----------------------------------------------------------------------------------
-constexpr int kLwThreads = 256;
-constexpr int kLwRB = 256;                          // hidden rows per workgroup (4 waves x 64)
+constexpr int kLwThreads = 512;
+constexpr int kLwRB = kLwThreads;                   // hidden rows per workgroup (64 per wave)
+constexpr int kLwStage = kLmVB * 8 / kLwThreads;     // 16-byte loads per thread and weight slice (128 rows x 8)
+constexpr int kLwStageRows = kLwThreads / 8;        // rows covered by one such load of the workgroup
+static_assert(kLwStage * kLwStageRows == kLmVB && kLwStage * kLwThreads * 16 == kLmVB * kLmKC * 2, "staging covers one weight slice exactly");
 constexpr int kLwLds = 2 * kLmHidBuf;               // two weight slices of 128 entries
 
 __global__ __launch_bounds__(256) void lm_pack_hidden_kernel(const uint16_t* __restrict__ hidden, int rows, int K,
@@ -250,7 +258,7 @@ __global__ __launch_bounds__(256) void lm_pack_hidden_kernel(const uint16_t* __r
   packed[idx] = v;
 }
 
-__global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P, const lm_u32x4* __restrict__ packed) {
+__global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, const lm_u32x4* __restrict__ packed) {
   extern __shared__ __align__(16) unsigned char lm_lds[];
   const int id = blockIdx.x;
   const int logical = (id & 7) * P.per_xcd + (id >> 3);
@@ -266,14 +274,14 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
   const int nch = P.K / kLmKC;
 
   // weight slice: 128 entries x 128 bytes, 8 lanes per row
-  const uint16_t* wsrc[4];
-  int wdst[4];
+  const uint16_t* wsrc[kLwStage];
+  int wdst[kLwStage];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int vrow = v0 + (tid >> 3) + 32 * j;
+  for (int j = 0; j < kLwStage; ++j) {
+    int vrow = v0 + (tid >> 3) + kLwStageRows * j;
     vrow = vrow < P.V ? vrow : P.V - 1;
     wsrc[j] = P.weight + static_cast<int64_t>(vrow) * P.K + (tid & 7) * 8;
-    wdst[j] = ((tid >> 3) + 32 * j) * kLmPitch + (tid & 7) * 16;
+    wdst[j] = ((tid >> 3) + kLwStageRows * j) * kLmPitch + (tid & 7) * 16;
   }
   // packed hidden operands of this wave's two row tiles (a wave without rows reads tile 0)
   const int tile0 = ntc > 0 ? (r0 >> 5) : 0;
@@ -299,26 +307,32 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
     // with less work (the last row block) would otherwise sit out a full load latency per slice.
     constexpr int PF = NT == 2 ? 2 : 4;
     constexpr int R = PF - 1;
-    lm_u32x4 wring[R][4];
-    auto load_weight = [&](int c, lm_u32x4 (&w)[4]) {
+    lm_u32x4 wring[R][kLwStage];
+    auto load_weight = [&](int c, lm_u32x4 (&w)[kLwStage]) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) w[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
+      for (int j = 0; j < kLwStage; ++j) w[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
     };
-    auto store_weight = [&](int buf, const lm_u32x4 (&w)[4]) {
+    auto store_weight = [&](int buf, const lm_u32x4 (&w)[kLwStage]) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) *reinterpret_cast<lm_u32x4*>(lm_lds + buf * kLmHidBuf + wdst[j]) = w[j];
+      for (int j = 0; j < kLwStage; ++j) *reinterpret_cast<lm_u32x4*>(lm_lds + buf * kLmHidBuf + wdst[j]) = w[j];
     };
     const int last = nch - 1;
-    lm_u32x4 b[2][4];
+    // Hidden operands: slice s lives in set s mod R.  With two row tiles there is one set, reloaded
+    // step by step with the next slice; with one tile there are three, so that this wave, which has
+    // half the matrix work per slice, does not wait a load latency per slice either.
+    lm_u32x4 b[R][2][4];
     {
-      lm_u32x4 w0[4];
+      lm_u32x4 w0[kLwStage];
       load_weight(0, w0);
       if constexpr (NT > 0) {
-        // same order as in the loop (step by step), so that the loop's wait counts stay tight
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int r = 0; r < R; ++r) {
+          const int cs = r < last ? r : last;
 #pragma unroll
-          for (int ni = 0; ni < NT; ++ni) b[ni][j] = hsrc[ni][j * 64];
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni) b[r][ni][j] = hsrc[ni][(cs * 4 + j) * 64];
+        }
       }
       store_weight(0, w0);
     }
@@ -334,12 +348,12 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
         const int c = c0 + r;
         if (c < nch) {
           const int buf = c & 1;
-          const int c1 = c < last ? c + 1 : last;
+          const int cb = c + R < last ? c + R : last;
           const int cp = c + PF < last ? c + PF : last;
           if constexpr (NT > 0) {
             const unsigned char* wrd = lm_lds + buf * kLmHidBuf + ln * kLmPitch + lh * 64;
             // weight operands are read one step ahead; a step's hidden operands are dead after its
-            // matrix instructions and are reloaded at once with the next slice's
+            // matrix instructions and are reloaded at once with those of R slices later
             lm_u32x4 a[2][4];
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi) a[0][mi] = *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch);
@@ -353,13 +367,13 @@ __global__ __launch_bounds__(kLwThreads, 2) void lm_head_wide_kernel(LmParams P,
 #pragma unroll
               for (int mi = 0; mi < 4; ++mi) {
                 acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][mi]),
-                                                                     __builtin_bit_cast(lm_bf16x8, b[0][j]), acc[mi][0], 0, 0, 0);
+                                                                     __builtin_bit_cast(lm_bf16x8, b[r][0][j]), acc[mi][0], 0, 0, 0);
                 if constexpr (NT > 1)
                   acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][mi]),
-                                                                       __builtin_bit_cast(lm_bf16x8, b[1][j]), acc[mi][1], 0, 0, 0);
+                                                                       __builtin_bit_cast(lm_bf16x8, b[r][1][j]), acc[mi][1], 0, 0, 0);
               }
 #pragma unroll
-              for (int ni = 0; ni < NT; ++ni) b[ni][j] = hsrc[ni][(c1 * 4 + j) * 64];
+              for (int ni = 0; ni < NT; ++ni) b[r][ni][j] = hsrc[ni][(cb * 4 + j) * 64];
               __builtin_amdgcn_sched_barrier(0);
             }
           }
