@@ -15,8 +15,8 @@
 // next to each other on one XCD so that a weight tile is served by that XCD's L2.
 //
 // Both operands are staged global -> registers -> LDS in 64-wide slices of the contraction
-// (rows padded to 144 bytes: conflict-free 16-byte operand reads), one slice ahead, one barrier per
-// slice.  Weight slices are private to their wave; hidden slices are shared by the four waves of a
+// (rows padded to 144 bytes: conflict-free 16-byte operand reads), the weights three slices ahead,
+// one barrier per slice.  Weight slices are private to their wave; hidden slices are shared by the four waves of a
 // half.
 #include <stdlib.h>
 
@@ -96,18 +96,22 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
     hsrc[j] = P.hidden + static_cast<int64_t>(hrow) * P.K + kbase + (t & 7) * 8;
     hdst[j] = ((t >> 3) + 32 * j) * kLmPitch + (t & 7) * 16;
   }
-  lm_u32x4 wreg[4], hreg[4];
-  auto load_slice = [&](int c) {
+  // Weight slices (HBM) are fetched three slices ahead into a ring of two register sets (slice s in
+  // set (s - 1) % 2); hidden slices (L2) one slice ahead.  Loads past the end repeat the last slice
+  // and are never used: a branch around a load would make the wait counts after it pessimistic.
+  lm_u32x4 wring[2][4], hreg[4];
+  auto load_w = [&](int c, lm_u32x4 (&w)[4]) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      wreg[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
-      hreg[j] = *reinterpret_cast<const lm_u32x4*>(hsrc[j] + c * kLmKC);
-    }
+    for (int j = 0; j < 4; ++j) w[j] = *reinterpret_cast<const lm_u32x4*>(wsrc[j] + c * kLmKC);
   };
-  auto store_slice = [&](int buf) {
+  auto load_h = [&](int c) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) hreg[j] = *reinterpret_cast<const lm_u32x4*>(hsrc[j] + c * kLmKC);
+  };
+  auto store_slice = [&](int buf, const lm_u32x4 (&w)[4]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      *reinterpret_cast<lm_u32x4*>(wst + buf * kLmWBuf + wdst[j]) = wreg[j];
+      *reinterpret_cast<lm_u32x4*>(wst + buf * kLmWBuf + wdst[j]) = w[j];
       *reinterpret_cast<lm_u32x4*>(hid + buf * kLmHidBuf + hdst[j]) = hreg[j];
     }
   };
@@ -118,27 +122,38 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
 
-  load_slice(0);
-  store_slice(0);
-  if (nch > 1) load_slice(1);
+  const int last = nch - 1;
+  load_w(0, wring[0]);
+  load_h(0);
+  store_slice(0, wring[0]);
+  load_w(1 < last ? 1 : last, wring[0]);
+  load_w(2 < last ? 2 : last, wring[1]);
+  load_h(1 < last ? 1 : last);
   __syncthreads();
-  for (int c = 0; c < nch; ++c) {
-    const int buf = c & 1;
-    const unsigned char* wrd = wst + buf * kLmWBuf + ln * kLmPitch + lh * 16;
-    const unsigned char* hrd = hid + buf * kLmHidBuf + ln * kLmPitch + lh * 16;
+  for (int c0 = 0; c0 < nch; c0 += 2) {
 #pragma unroll
-    for (int s = 0; s < kLmKC / 16; ++s) {
-      const lm_bf16x8 a = __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(wrd + 32 * s));
+    for (int r = 0; r < 2; ++r) {
+      const int c = c0 + r;
+      if (c < nch) {
+        const int buf = c & 1;
+        const unsigned char* wrd = wst + buf * kLmWBuf + ln * kLmPitch + lh * 16;
+        const unsigned char* hrd = hid + buf * kLmHidBuf + ln * kLmPitch + lh * 16;
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) {
-        const lm_bf16x8 b =
-            __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(hrd + nt * 32 * kLmPitch + 32 * s));
-        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+        for (int s = 0; s < kLmKC / 16; ++s) {
+          const lm_bf16x8 a = __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(wrd + 32 * s));
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) {
+            const lm_bf16x8 b =
+                __builtin_bit_cast(lm_bf16x8, *reinterpret_cast<const lm_u32x4*>(hrd + nt * 32 * kLmPitch + 32 * s));
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+          }
+        }
+        store_slice(buf ^ 1, wring[r]);                       // slice c + 1
+        load_w(c + 3 < last ? c + 3 : last, wring[r]);
+        load_h(c + 2 < last ? c + 2 : last);
+        __syncthreads();
       }
     }
-    if (c + 1 < nch) store_slice(buf ^ 1);
-    if (c + 2 < nch) load_slice(c + 2);
-    __syncthreads();
   }
 
   // add the two halves of the contraction: the upper half hands its tile over through LDS
