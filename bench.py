@@ -271,7 +271,9 @@ def main():
         bound = "hbm" if hbm_time >= mfma_time else "mfma"
         ach = lm_bytes / lm_s / 1e9 if bound == "hbm" else lm_flops / lm_s / 1e12
         peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS
-        lm_obj = {"kernel": "spec_lm_head: lm_head_kernel + lm_stats_merge_kernel (duration is the whole call)",
+        lm_kernel = ("lm_head_kernel (up to 128 rows: weight matrix read once)" if rows <= 128 else
+                     "lm_pack_hidden_kernel + lm_head_wide_kernel (512 rows per workgroup)")
+        lm_obj = {"kernel": f"spec_lm_head: {lm_kernel} + lm_stats_merge_kernel; duration is the whole call",
                   "rows": rows, "d_model": cfg.d_model, "vocab": cfg.vocab, "launch_us_mean": lm_s * 1e6,
                   "roofline": {"bound": bound, "achieved": ach, "peak": peak,
                                "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak,
