@@ -167,3 +167,42 @@ def test_accept_prestats_with_probability_rows(rt):
     dev.run_prestats()
     bad, ties, B = compare_accept(dev.results(), ref, st.n)
     assert not bad and ties <= 1
+
+
+@pytest.mark.parametrize("rows,d_model,V,T", [
+    (72, 4096, 32000, 1.0),        # c1's target rows on the Llama-2-7B head: the weight-read-bound kernel
+    (1040, 4096, 128256, 1.0),     # c2's target rows on the Llama-3-8B head: packed hidden states, 512-row blocks
+])
+def test_lm_head_full_size_sampled(rt, rows, d_model, V, T):
+    """Benchmark shapes in the launch configuration bench.py times.  The oracle evaluates a sample of
+    (row, vocabulary entry) pairs one by one - tile borders, the first and last entries, random ones;
+    the statistics are checked, for every row, against an fp64 evaluation of the kernel's own logits
+    (library reductions on the device: a property that holds at any size)."""
+    li = W.make_lm_head_inputs(rows, d_model, V, seed=7)
+    dev = rt.DeviceLmHead(li, temperature=T)
+    dev.run()
+    got_bits = dev.logits_bits()
+    rng = np.random.default_rng(11)
+    rsel = sorted(set([0, rows - 1, min(rows - 1, 31), min(rows - 1, 32), min(rows - 1, 63), min(rows - 1, 64),
+                       min(rows - 1, 511), min(rows - 1, 512), min(rows - 1, 1023), min(rows - 1, 1024)]
+                      + rng.integers(0, rows, size=14).tolist()))
+    vsel = sorted(set([0, 1, 31, 32, 127, 128, 8191, 8192, V - 129, V - 128, V - 2, V - 1]
+                      + rng.integers(0, V, size=52).tolist()))
+    ref = oracle.lm_head(li.hidden[rsel], li.weight[vsel], temperature=T, want_exact=True)
+    got = W.bf16_bits_to_f32(got_bits[np.ix_(rsel, vsel)]).astype(np.float64)
+    absprod = (np.abs(W.bf16_bits_to_f32(li.hidden[rsel])).astype(np.float64)
+               @ np.abs(W.bf16_bits_to_f32(li.weight[vsel])).astype(np.float64).T)
+    tol = np.abs(ref["exact"]) * 2.0 ** -8 + 1e-5 * absprod
+    assert np.all(np.abs(got - ref["exact"]) <= tol)
+    assert np.mean(got_bits[np.ix_(rsel, vsel)] != ref["logits"]) < 2e-2
+    # every row's statistics against the kernel's own logits
+    m, z = dev.segment_stats()
+    lg = dev.logits.double()
+    nseg = (V + 8191) // 8192
+    for s in range(nseg):
+        seg = lg[:, s * 8192:(s + 1) * 8192]
+        mx = seg.max(dim=1).values
+        zr = torch.exp((seg - mx[:, None]) / T).sum(dim=1)
+        assert np.array_equal(m[:, s].astype(np.float64), mx.cpu().numpy()), f"segment {s} maximum"
+        assert np.max(np.abs(z[:, s] - zr.cpu().numpy()) / zr.cpu().numpy()) < 3e-6, f"segment {s} sum"
+    assert torch.isfinite(lg).all()
