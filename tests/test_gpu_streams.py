@@ -79,3 +79,45 @@ def test_two_streams_do_not_interfere(rt):
                              ai.u_accept, ai.u_resample)
         bad, ties, B = compare_accept(acc.results(), want, a.st.n)
         assert not bad
+
+
+@pytest.mark.parametrize("rows_extra", [0, 150])       # the weight-read-bound kernel; the packed-hidden kernel
+def test_graph_replay_lm_head_then_accept(rt, rows_extra):
+    """spec_lm_head + spec_accept_prestats captured into one HIP graph: every replay reproduces the eager
+    logits, statistics and acceptance results, with stale bytes in all scratch memory in between."""
+    cfg = W.scaled(C["c1_llama2_7b"], batch=6, vocab=9000, draft=("linear_uniform", 2, 6))
+    st = W.make_structure(cfg, seed=3)
+    rows = st.total + cfg.batch
+    li = W.make_lm_head_inputs(rows + rows_extra, 256, cfg.vocab, seed=3)     # extra rows: hidden states nobody verifies
+    ai = W.make_accept_inputs(cfg, seed=3, st=st)
+    ws = torch.zeros(max(rt.sv.spec_accept_workspace_size(cfg.batch, st.total, ai.draft_q.shape[0], cfg.vocab),
+                         rt.sv.spec_row_stats_size(rows + rows_extra, cfg.vocab)), dtype=torch.uint8, device="cuda")
+    head = rt.DeviceLmHead(li, stats=ws)
+    acc = rt.DeviceAccept(st, head.logits[:rows], ai.draft_q, ai.q_row, ai.draft_tokens, ai.u_accept, ai.u_resample)
+    acc.workspace = ws
+    head.run(); acc.run_prestats()
+    torch.cuda.synchronize()
+    logits0, stats0 = head.logits.clone(), ws[: rt.sv.spec_row_stats_size(rows, cfg.vocab)].clone()
+    res0 = {k: v.copy() for k, v in acc.results().items() if v is not None}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            head.run(); acc.run_prestats()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        head.logits.zero_(); head.workspace.fill_(0xEE); ws.fill_(0xEE)
+        acc.accept_len.fill_(-9); acc.out_tokens.fill_(-9)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(head.logits, logits0), rep
+        assert torch.equal(ws[: stats0.numel()], stats0), rep
+        res = acc.results()
+        for k, v in res0.items():
+            assert np.array_equal(res[k], v, equal_nan=True), (rep, k)
+    want = oracle.accept(st.node_offsets, st.parent, ai.draft_tokens, head.logits_bits()[:rows], ai.draft_q, ai.q_row,
+                         ai.u_accept, ai.u_resample)
+    bad, ties, B = compare_accept(res0, want, st.n)
+    assert not bad and ties <= 1
