@@ -273,6 +273,7 @@ __global__ __launch_bounds__(256) void lm_pack_hidden_kernel(const uint16_t* __r
   packed[idx] = v;
 }
 
+template <int PF2>
 __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, const lm_u32x4* __restrict__ packed) {
   extern __shared__ __align__(16) unsigned char lm_lds[];
   const int id = blockIdx.x;
@@ -315,13 +316,17 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
   // The whole slice loop exists three times - two, one or no row tile in this wave - and one scalar
   // branch picks the copy: branches inside the loop would split the accumulators' live ranges.
   // Every copy passes the same barriers.
-  auto slice_loop = [&](auto n_tiles) {
+  auto slice_loop = [&](auto n_tiles, auto ahead) {
     constexpr int NT = decltype(n_tiles)::value;
-    // Weight slices are fetched PF slices ahead into a ring of PF - 1 register sets.  A wave with two
-    // row tiles has registers for one set and enough matrix work per slice to cover the load; waves
-    // with less work (the last row block) would otherwise sit out a full load latency per slice.
-    constexpr int PF = NT == 2 ? 2 : 4;
+    // Weight slices are fetched PF slices ahead into a ring of PF - 1 register sets (8 registers per
+    // set).  With up to 256 rows the product is bound by streaming the weights from HBM and two slices
+    // ahead is a load latency short (kernel instance PF2 = 4); with more rows it is bound by the
+    // matrix cores and the shorter ring measured faster (PF2 = 2).  Waves of a partial block have
+    // little matrix work per slice to hide a load behind and always use the deep ring.  Hidden
+    // operands: one set per HB slices ahead.
+    constexpr int PF = decltype(ahead)::value;
     constexpr int R = PF - 1;
+    constexpr int HB = NT == 2 ? 1 : R;
     lm_u32x4 wring[R][kLwStage];
     auto load_weight = [&](int c, lm_u32x4 (&w)[kLwStage]) {
 #pragma unroll
@@ -332,16 +337,16 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
       for (int j = 0; j < kLwStage; ++j) *reinterpret_cast<lm_u32x4*>(lm_lds + buf * kLmHidBuf + wdst[j]) = w[j];
     };
     const int last = nch - 1;
-    // Hidden operands: slice s lives in set s mod R.  With two row tiles there is one set, reloaded
+    // Hidden operands: slice s lives in set s mod HB.  With two row tiles there is one set, reloaded
     // step by step with the next slice; with one tile there are three, so that this wave, which has
     // half the matrix work per slice, does not wait a load latency per slice either.
-    lm_u32x4 b[R][2][4];
+    lm_u32x4 b[HB][2][4];
     {
       lm_u32x4 w0[kLwStage];
       load_weight(0, w0);
       if constexpr (NT > 0) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
+        for (int r = 0; r < HB; ++r) {
           const int cs = r < last ? r : last;
 #pragma unroll
           for (int j = 0; j < 4; ++j)
@@ -363,12 +368,12 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
         const int c = c0 + r;
         if (c < nch) {
           const int buf = c & 1;
-          const int cb = c + R < last ? c + R : last;
+          const int cb = c + HB < last ? c + HB : last;
           const int cp = c + PF < last ? c + PF : last;
           if constexpr (NT > 0) {
             const unsigned char* wrd = lm_lds + buf * kLmHidBuf + ln * kLmPitch + lh * 64;
             // weight operands are read one step ahead; a step's hidden operands are dead after its
-            // matrix instructions and are reloaded at once with those of R slices later
+            // matrix instructions and are reloaded at once with those of HB slices later
             lm_u32x4 a[2][4];
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi) a[0][mi] = *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch);
@@ -382,13 +387,13 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
 #pragma unroll
               for (int mi = 0; mi < 4; ++mi) {
                 acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][mi]),
-                                                                     __builtin_bit_cast(lm_bf16x8, b[r][0][j]), acc[mi][0], 0, 0, 0);
+                                                                     __builtin_bit_cast(lm_bf16x8, b[r % HB][0][j]), acc[mi][0], 0, 0, 0);
                 if constexpr (NT > 1)
                   acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][mi]),
-                                                                       __builtin_bit_cast(lm_bf16x8, b[r][1][j]), acc[mi][1], 0, 0, 0);
+                                                                       __builtin_bit_cast(lm_bf16x8, b[r % HB][1][j]), acc[mi][1], 0, 0, 0);
               }
 #pragma unroll
-              for (int ni = 0; ni < NT; ++ni) b[r][ni][j] = hsrc[ni][(cb * 4 + j) * 64];
+              for (int ni = 0; ni < NT; ++ni) b[r % HB][ni][j] = hsrc[ni][(cb * 4 + j) * 64];
               __builtin_amdgcn_sched_barrier(0);
             }
           }
@@ -399,9 +404,10 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
       }
     }
   };
-  if (ntc == 2) slice_loop(std::integral_constant<int, 2>{});
-  else if (ntc == 1) slice_loop(std::integral_constant<int, 1>{});
-  else slice_loop(std::integral_constant<int, 0>{});
+  using Deep = std::integral_constant<int, 4>;
+  if (ntc == 2) slice_loop(std::integral_constant<int, 2>{}, std::integral_constant<int, PF2>{});
+  else if (ntc == 1) slice_loop(std::integral_constant<int, 1>{}, Deep{});
+  else slice_loop(std::integral_constant<int, 0>{}, Deep{});
 
   // each wave holds all 128 vocabulary entries of the block for its rows: statistics need no LDS
   const bool vec4 = (P.V & 3) == 0;
@@ -517,7 +523,10 @@ int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
     const int64_t n_items = static_cast<int64_t>((a.rows + 31) / 32) * (a.d_model / kLmKC) * 256;
     hipLaunchKernelGGL(lm_pack_hidden_kernel, dim3(static_cast<unsigned>((n_items + 255) / 256)), dim3(256), 0, stream,
                        P.hidden, a.rows, a.d_model, n_items, packed);
-    hipLaunchKernelGGL(lm_head_wide_kernel, dim3(P.per_xcd * 8), dim3(kLwThreads), kLwLds, stream, P, packed);
+    if (a.rows <= 256)
+      hipLaunchKernelGGL(lm_head_wide_kernel<4>, dim3(P.per_xcd * 8), dim3(kLwThreads), kLwLds, stream, P, packed);
+    else
+      hipLaunchKernelGGL(lm_head_wide_kernel<2>, dim3(P.per_xcd * 8), dim3(kLwThreads), kLwLds, stream, P, packed);
   } else {
     hipLaunchKernelGGL(lm_head_kernel, dim3(P.per_xcd * 8), dim3(kLmThreads), kLmLds, stream, P);
   }
