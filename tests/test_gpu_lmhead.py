@@ -81,6 +81,13 @@ def test_lm_head_matches_oracle(rt, rows, d_model, V, T):
     print(f"rows {rows} d {d_model} V {V}: bf16 neighbours chosen differently in {mismatch:.2e} of the entries")
 
 
+@pytest.mark.parametrize("rows", [127, 128, 129, 255, 256, 257, 511, 512, 513, 600])
+def test_lm_head_row_count_boundaries(rt, rows):
+    """Row counts around every switch of kernel, prefetch depth and row block (128, 256, 512), with a
+    vocabulary that ends inside a tile."""
+    check_lm_head(rt, rows, 128, 300, 1.0, seed=rows)
+
+
 def test_lm_head_is_deterministic_and_leaves_neighbours_alone(rt):
     li = W.make_lm_head_inputs(37, 384, 2500, seed=3)
     dev = rt.DeviceLmHead(li)
