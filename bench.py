@@ -277,6 +277,7 @@ def main():
                   "rows": rows, "d_model": cfg.d_model, "vocab": cfg.vocab, "launch_us_mean": lm_s * 1e6,
                   "roofline": {"bound": bound, "achieved": ach, "peak": peak,
                                "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak,
+                               "traffic": read_traffic("lm_head_c1") if cfg.name == "c1_llama2_7b" else None,
                                "algorithmic_bytes": lm_bytes, "flops": lm_flops}}
     if args.calibration_copy_mb > 0:
         # a plain copy kernel of known size: reads N MiB and writes N MiB
