@@ -154,7 +154,7 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None):
         oracle.lm_head(lm.hidden[:r], lm.weight, temperature=cfg.temperature)
         lm_s = (time.perf_counter() - t0) * rows / r
         lm_note = f"; plus the projection, timed on {r} of {rows} rows and scaled: {lm_s:.2f} s per pass"
-    while reps < 1 or (t_total < budget_s and reps < 50):
+    while reps < 1 or (t_total < budget_s and reps < 1000):
         t0 = time.perf_counter()
         oracle.verify_attn(a.q, a.k_pool, a.v_pool, a.block_table, a.st.ctx_len, a.st.node_offsets,
                            a.st.parent, want_lse=False)
