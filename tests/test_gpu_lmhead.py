@@ -102,19 +102,37 @@ def test_lm_head_is_deterministic_and_leaves_neighbours_alone(rt):
     assert bool((guard == 7).all())
 
 
+def pipeline_agrees(got, ref, st, toks, gpu_bits, ref_bits, max_disagree=1):
+    """The GPU pipeline (spec_lm_head -> acceptance) against the oracle's (oracle.lm_head ->
+    oracle.accept), both fed the same host inputs.  The two sets of logits are bf16 neighbours in
+    about one entry in ten thousand; a request none of whose drafted (row, token) logits is such an
+    entry must decide exactly as the oracle does (outside the oracle's near-ties), and at most
+    ``max_disagree`` requests may contain one."""
+    disagree = []
+    for b in range(len(st.n)):
+        o, n = int(st.node_offsets[b]), int(st.n[b])
+        for j in range(n):
+            par = j - 1 if st.parent is None else int(st.parent[o + j])
+            r = o + b + 1 + par
+            if gpu_bits[r, toks[o + j]] != ref_bits[r, toks[o + j]]:
+                disagree.append(b)
+                break
+    bad, ties, B = compare_accept(got, ref, st.n)
+    assert set(bad) <= set(disagree), (bad, disagree)
+    assert len(disagree) <= max_disagree
+    return ties
+
+
 def test_accept_from_lm_head_statistics(rt):
     """hidden x weight -> logits + statistics (one kernel family), then the walk from those
-    statistics: same decisions as spec_accept on the same logits, and as the oracle's walk."""
+    statistics.  Reference: the oracle's own pipeline on the same host inputs.  The prestats entry
+    must also decide exactly like spec_accept on the same device logits."""
     T = 0.9
     cfg = W.scaled(W.CONFIGS["c1_llama2_7b"], batch=10, vocab=9000, draft=("linear_uniform", 2, 7), temperature=T)
     st = W.make_structure(cfg, seed=1)
     rows = st.total + cfg.batch
     li = W.make_lm_head_inputs(rows, 512, cfg.vocab, seed=1)
-    ws = torch.zeros(rt.sv.spec_accept_workspace_size(cfg.batch, st.total, st.total, cfg.vocab), dtype=torch.uint8,
-                     device="cuda")
-    head = rt.DeviceLmHead(li, temperature=T, stats=ws)
-    head.run()
-    tl = head.logits_bits()
+    tl = oracle.lm_head(li.hidden, li.weight, temperature=T)["logits"]
     # drafts: node j of request b is drawn from a noisy copy of the target row it will be compared with
     rng = np.random.default_rng(5)
     q = np.zeros((st.total, cfg.vocab), dtype=np.uint16)
@@ -130,6 +148,10 @@ def test_accept_from_lm_head_statistics(rt):
     u_res = W.uniforms24(rng, cfg.batch)
     ref = oracle.accept(st.node_offsets, None, toks, tl, q, q_row, u_acc, u_res, temperature=T, qkind=0)
 
+    ws = torch.zeros(rt.sv.spec_accept_workspace_size(cfg.batch, st.total, st.total, cfg.vocab), dtype=torch.uint8,
+                     device="cuda")
+    head = rt.DeviceLmHead(li, temperature=T, stats=ws)
+    head.run()
     pre = rt.DeviceAccept(st, head.logits, q, q_row, toks, u_acc, u_res, temperature=T)
     pre.workspace = ws
     pre.run_prestats()
@@ -138,14 +160,13 @@ def test_accept_from_lm_head_statistics(rt):
     plain.run()
     got_plain = plain.results()
 
-    for got in (got_pre, got_plain):
-        bad, ties, B = compare_accept(got, ref, st.n)
-        assert not bad and ties <= 2
-        assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+    ties = pipeline_agrees(got_pre, ref, st, toks, head.logits_bits(), tl)
+    assert ties <= 2
     assert ref["accept_len"].max() >= 2 and ref["accept_len"].min() < st.n.max()
-    if not ref["near_tie"].any():
-        for key in ("accept_len", "out_tokens", "stop_node"):
-            assert np.array_equal(got_pre[key], got_plain[key]), key
+    # fused statistics against a second pass over the same device logits: same walk
+    for key in ("accept_len", "out_tokens", "stop_node"):
+        assert np.array_equal(got_pre[key], got_plain[key]), key
+    assert ratio_err(got_pre["ratio"], got_plain["ratio"].astype(np.float64)) < 5e-6
 
 
 def test_accept_prestats_with_probability_rows(rt):
@@ -156,12 +177,7 @@ def test_accept_prestats_with_probability_rows(rt):
     st = W.make_structure(cfg, seed=2)
     rows = st.total + cfg.batch
     li = W.make_lm_head_inputs(rows, 256, cfg.vocab, seed=2)
-    ws = torch.zeros(rt.sv.spec_accept_workspace_size(cfg.batch, st.total, st.total, cfg.vocab), dtype=torch.uint8,
-                     device="cuda")
-    ws.fill_(0xAB)                                   # stale bytes: everything the walk reads must be rewritten
-    head = rt.DeviceLmHead(li, temperature=T, stats=ws)
-    head.run()
-    tl = head.logits_bits()
+    tl = oracle.lm_head(li.hidden, li.weight, temperature=T)["logits"]
     rng = np.random.default_rng(6)
     qp = rng.dirichlet(np.full(cfg.vocab, 0.05), size=st.total).astype(np.float32)
     toks = np.array([rng.choice(cfg.vocab, p=qp[j].astype(np.float64) / qp[j].astype(np.float64).sum())
@@ -169,11 +185,16 @@ def test_accept_prestats_with_probability_rows(rt):
     q_row = np.arange(st.total, dtype=np.int32)
     u_acc, u_res = W.uniforms24(rng, st.total), W.uniforms24(rng, cfg.batch)
     ref = oracle.accept(st.node_offsets, None, toks, tl, qp, q_row, u_acc, u_res, temperature=T, qkind=1)
+
+    ws = torch.zeros(rt.sv.spec_accept_workspace_size(cfg.batch, st.total, st.total, cfg.vocab), dtype=torch.uint8,
+                     device="cuda")
+    ws.fill_(0xAB)                                   # stale bytes: everything the walk reads must be rewritten
+    head = rt.DeviceLmHead(li, temperature=T, stats=ws)
+    head.run()
     dev = rt.DeviceAccept(st, head.logits, qp, q_row, toks, u_acc, u_res, temperature=T, q_kind=1)
     dev.workspace = ws
     dev.run_prestats()
-    bad, ties, B = compare_accept(dev.results(), ref, st.n)
-    assert not bad and ties <= 1
+    assert pipeline_agrees(dev.results(), ref, st, toks, head.logits_bits(), tl) <= 1
 
 
 @pytest.mark.parametrize("rows,d_model,V,T", [

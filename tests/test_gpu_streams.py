@@ -117,7 +117,15 @@ def test_graph_replay_lm_head_then_accept(rt, rows_extra):
         res = acc.results()
         for k, v in res0.items():
             assert np.array_equal(res[k], v, equal_nan=True), (rep, k)
-    want = oracle.accept(st.node_offsets, st.parent, ai.draft_tokens, head.logits_bits()[:rows], ai.draft_q, ai.q_row,
-                         ai.u_accept, ai.u_resample)
+    # reference: the oracle's own pipeline on the same host inputs; requests whose drafted logits are
+    # bf16 neighbours on the two sides (about one entry in ten thousand is) are exempt
+    tl = oracle.lm_head(li.hidden[:rows], li.weight)["logits"]
+    want = oracle.accept(st.node_offsets, st.parent, ai.draft_tokens, tl, ai.draft_q, ai.q_row, ai.u_accept,
+                         ai.u_resample)
+    gpu_bits = head.logits_bits()
+    disagree = [b for b in range(cfg.batch)
+                if any(gpu_bits[int(st.node_offsets[b]) + b + j, ai.draft_tokens[int(st.node_offsets[b]) + j]] !=
+                       tl[int(st.node_offsets[b]) + b + j, ai.draft_tokens[int(st.node_offsets[b]) + j]]
+                       for j in range(int(st.n[b])))]
     bad, ties, B = compare_accept(res0, want, st.n)
-    assert not bad and ties <= 1
+    assert set(bad) <= set(disagree) and len(disagree) <= 1 and ties <= 1
