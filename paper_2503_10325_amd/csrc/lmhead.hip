@@ -49,6 +49,7 @@ static_assert(kLmBlocksPerSeg == 64, "one wave merges one segment");
 struct LmParams {
   int rows, K, V;
   int nvb, nrb, total, per_xcd;
+  int panel;               // wide kernel: vocabulary blocks per panel (0: row blocks of a vocabulary block adjacent)
   float c;
   const uint16_t* hidden;
   const uint16_t* weight;
@@ -247,9 +248,9 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
 // lane L holding hidden[32 tile + L % 32][64 slice + 32 (L / 32) + 8 j .. + 8]; rows past the end
 // are zero.
 //
-// A last row block with few rows costs more than its rows: its workgroups run ahead of their
-// siblings and stream the weight matrix from HBM once more (they overlap with the matrix-bound full
-// blocks, but the row count at which the product is cheapest per row is a multiple of 512).
+// A last row block with few rows costs more than its rows: each of its workgroups holds a CU while
+// it streams a whole weight tile for one or two row tiles of matrix work (the row count at which the
+// product is cheapest per row is a multiple of 512).
 // ----------------------------------------------------------------------------------
 constexpr int kLwThreads = 512;
 constexpr int kLwRB = kLwThreads;                   // hidden rows per workgroup (64 per wave)
@@ -277,9 +278,22 @@ template <int PF2>
 __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, const lm_u32x4* __restrict__ packed) {
   extern __shared__ __align__(16) unsigned char lm_lds[];
   const int id = blockIdx.x;
-  const int logical = (id & 7) * P.per_xcd + (id >> 3);
-  if (logical >= P.total) return;
-  const int rbk = logical % P.nrb, vb = logical / P.nrb;
+  int rbk, vb;
+  if (P.panel > 0) {
+    // vocabulary panels small enough for the memory-side cache: inside a panel all workgroups of row
+    // block 0 come first, then row block 1 ... (consecutive ids spread over all XCDs), so that the
+    // panel's weights are read from HBM once and by the later row blocks from that cache
+    if (id >= P.total) return;
+    const int per_panel = P.panel * P.nrb;
+    const int pn = id / per_panel, rem = id - pn * per_panel;
+    const int width = min(P.panel, P.nvb - pn * P.panel);
+    rbk = rem / width;
+    vb = pn * P.panel + rem - rbk * width;
+  } else {
+    const int logical = (id & 7) * P.per_xcd + (id >> 3);
+    if (logical >= P.total) return;
+    rbk = logical % P.nrb; vb = logical / P.nrb;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   const int v0 = vb * kLmVB;
@@ -513,6 +527,14 @@ int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
   P.nrb = (a.rows + (wide ? kLwRB : kLmRB) - 1) / (wide ? kLwRB : kLmRB);
   P.total = P.nvb * P.nrb;
   P.per_xcd = (P.total + 7) / 8;
+  // Several row blocks: panels of 128 vocabulary blocks (134 MB of weights at d_model = 4096), every
+  // row block of a panel in turn, measured 5-10 % faster than keeping the row blocks of one
+  // vocabulary block adjacent when the last row block is partial, and equal otherwise.
+  P.panel = (wide && P.nrb > 1) ? 128 : 0;
+  if (const char* e = getenv("SPECV_LM_PANEL")) {                       // development knob
+    const int v = atoi(e);
+    if (v >= 0 && v <= 65536) P.panel = v;
+  }
   P.c = kLog2e / a.temperature;
   P.hidden = static_cast<const uint16_t*>(a.hidden);
   P.weight = static_cast<const uint16_t*>(a.weight);
