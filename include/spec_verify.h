@@ -301,6 +301,14 @@ int32_t spec_compact_kv(
  * layout: pass the START of the workspace later given to spec_accept_prestats (with
  * the same temperature), or any device buffer of that size.  Any number of rows up to
  * 65535; up to 128 rows the weight matrix is read once.
+ * All pointers are device memory owned by the caller; the call only enqueues kernels on
+ * `stream` and allocates nothing.  workspace: spec_lm_head_workspace_size(rows,
+ * d_model, V) bytes (per-block statistics and, above 128 rows, the hidden states
+ * re-laid out in matrix-operand order); its contents need not survive the call.
+ * Errors: SPEC_ERR_SHAPE (negative or zero sizes, temperature <= 0, misaligned
+ * pointers), SPEC_ERR_UNSUPPORTED (d_model not a multiple of 128 or above 65536, V above
+ * 2097152, more than 65535 rows), SPEC_ERR_NULL, SPEC_ERR_WORKSPACE, SPEC_ERR_LAUNCH;
+ * rows == 0 is SPEC_OK and touches nothing.
  * ---------------------------------------------------------------------------- */
 size_t spec_row_stats_size(int32_t rows, int32_t V);
 size_t spec_lm_head_workspace_size(int32_t rows, int32_t d_model, int32_t V);
