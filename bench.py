@@ -47,6 +47,10 @@ def parse_args():
     ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
                     help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
                          "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
+    ap.add_argument("--fuse-mode", choices=["argmax", "mixture"], default="argmax",
+                    help="multi-drafter workloads: argmax = the paper's confidence rule (Eq. 4, the headline path); "
+                         "mixture = confidence-weighted average of the drafters' distributions (Section 2.2), written "
+                         "as fp32 probabilities that the acceptance step then reads as its draft rows")
     ap.add_argument("--lm-head", action="store_true",
                     help="also run the projection that produces the target logits (spec_lm_head on synthetic "
                          "[rows, d_model] hidden states and a [vocab, d_model] bf16 weight, d_model = heads x "
@@ -69,18 +73,25 @@ def read_traffic(workload):
 class Step:
     """Device state of one input copy and the three calls of one step."""
 
-    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto", routing=False, lm=None):
+    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto", routing=False, lm=None,
+                 fuse_mode="argmax"):
         import torch
         self.routing = None
         self.head = None
         self.attn = runner.DeviceAttn(a, want_lse=False)
         st = a.st
         if ai.fusion is not None:
-            self.fuse = runner.DeviceFuse(ai.fusion, cfg.vocab, temperature=cfg.temperature)
+            mixture = fuse_mode == "mixture"
+            self.fuse = runner.DeviceFuse(ai.fusion, cfg.vocab, temperature=cfg.temperature,
+                                          mode=sv.SPEC_FUSE_MIXTURE if mixture else sv.SPEC_FUSE_ARGMAX)
             assert int(st.n.min()) == int(st.n.max()), "fusion output is used as a flat [B*k] view"
-            self.accept = runner.DeviceAccept(st, ai.target_logits, self.fuse.draft_logits,
+            # ARGMAX: the draft rows are the drafters' logits, q_row picks the winner's; MIXTURE: the draft
+            # rows are the fused probabilities the fusion call writes (row b*k+i for node i of request b)
+            self.accept = runner.DeviceAccept(st, ai.target_logits,
+                                              self.fuse.fused_probs if mixture else self.fuse.draft_logits,
                                               self.fuse.q_row.view(-1), self.fuse.fused_token.view(-1),
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
+                                              q_kind=sv.SPEC_Q_PROBS if mixture else sv.SPEC_Q_LOGITS,
                                               want_debug=False)
         else:
             # single drafter: token fusion has nothing to fuse.  With --fuse always it still runs with
@@ -140,7 +151,7 @@ class Step:
             self.routing()
 
 
-def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None):
+def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None, fuse_mode="argmax"):
     """The oracle, as it stands, timed on the host cores over whole batches of the workload."""
     import oracle
     reps, t_total = 0, 0.0
@@ -158,7 +169,13 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None):
         t0 = time.perf_counter()
         oracle.verify_attn(a.q, a.k_pool, a.v_pool, a.block_table, a.st.ctx_len, a.st.node_offsets,
                            a.st.parent, want_lse=False)
-        if ai.fusion is not None:
+        qkind = oracle.Q_LOGITS
+        if ai.fusion is not None and fuse_mode == "mixture":
+            rf = oracle.fuse_drafts(ai.fusion.k_len, ai.fusion.conf, ai.fusion.draft_tokens, ai.fusion.draft_logits,
+                                    temperature=cfg.temperature, mode=oracle.FUSE_MIXTURE)
+            toks, qrow, dq = rf["fused_token"].reshape(-1), rf["q_row"].reshape(-1), rf["fused_probs"].astype(np.float32)
+            qkind = oracle.Q_PROBS
+        elif ai.fusion is not None:
             rf = oracle.fuse_drafts(ai.fusion.k_len, ai.fusion.conf, ai.fusion.draft_tokens)
             toks, qrow, dq = rf["fused_token"].reshape(-1), rf["q_row"].reshape(-1), ai.fusion.draft_logits
         else:
@@ -167,7 +184,7 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None):
             oracle.accept_greedy(a.st.node_offsets, a.st.parent, toks, ai.target_logits)
         else:
             oracle.accept(a.st.node_offsets, a.st.parent, toks, ai.target_logits, dq, qrow, ai.u_accept,
-                          ai.u_resample, temperature=cfg.temperature)
+                          ai.u_resample, temperature=cfg.temperature, qkind=qkind)
         t_total += time.perf_counter() - t0
         reps += 1
     return dict(value=tokens * reps / (t_total + reps * lm_s), unit="tokens/s", cores=oracle.num_threads(),
@@ -205,7 +222,7 @@ def main():
         ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st, target_logits=host_logits)
     else:
         ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
-    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse, args.routing, lm)
+    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse, args.routing, lm, args.fuse_mode)
               for _ in range(max(1, args.copies))]
     torch.cuda.synchronize()
 
@@ -293,6 +310,11 @@ def main():
     if args.accept_mode == "greedy":
         n_logit_rows = ai.target_logits.shape[0]          # no draft distributions are read
     accept_bytes = n_logit_rows * cfg.vocab * 2
+    if ai.fusion is not None and args.fuse_mode == "mixture" and args.accept_mode == "sampling":
+        # the drafters' rows are streamed twice by the fusion call (statistics, weighted sum), the fused fp32
+        # rows are written once and read once by the acceptance statistics
+        n_fused = ai.fusion.conf.shape[0] * ai.fusion.conf.shape[1]
+        accept_bytes = (ai.target_logits.shape[0] * 2 + ai.fusion.draft_logits.shape[0] * 2 * 2 + n_fused * 4 * 2) * cfg.vocab
     # the attention kernel the library's plan picks for this shape (all query rows that share a KV head)
     max_rows = int(a.st.n.max()) * (cfg.n_q_heads // cfg.n_kv_heads)
     total_tok = int((a.st.ctx_len.astype(np.int64) + a.st.n).sum())
@@ -320,6 +342,7 @@ def main():
         "data": "synthetic",
         "launch_mode": "eager" if graphs is None else "hip_graph_replay",
         "accept_mode": args.accept_mode,
+        "fuse_mode": args.fuse_mode if ai.fusion is not None else None,
         "calls_per_step": ["spec_verify_attn"] + (["spec_lm_head"] if lm is not None else []) +
                           (["spec_fuse_drafts"] if copies[0].fuse is not None else []) +
                           [("spec_accept_prestats" if lm is not None else "spec_accept")
@@ -340,7 +363,7 @@ def main():
     if lm_obj is not None:
         out["lm_head"] = lm_obj
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds, args.accept_mode, lm)
+        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds, args.accept_mode, lm, args.fuse_mode)
     print(json.dumps(out))
 
 
