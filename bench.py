@@ -317,7 +317,8 @@ def main():
 
     tokens = int(a.st.total)
     attn_bytes, attn_flops = W.attention_bytes_flops(cfg, a.st)
-    n_logit_rows = ai.target_logits.shape[0] + (ai.fusion.draft_logits.shape[0] if ai.fusion else ai.draft_q.shape[0])
+    # draft rows the statistics pass reads: with several drafters only the rows a fused token was drawn from
+    n_logit_rows = ai.target_logits.shape[0] + (int(a.st.total) if ai.fusion else ai.draft_q.shape[0])
     if args.accept_mode == "greedy":
         n_logit_rows = ai.target_logits.shape[0]          # no draft distributions are read
     accept_bytes = n_logit_rows * cfg.vocab * 2

@@ -30,7 +30,8 @@ template <bool VEC>
 __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
     const void* __restrict__ t_base, int t_dtype, int n_t_rows,
     const void* __restrict__ q_base, int q_dtype, int n_q_rows,
-    int V, float c, int nseg, SegStat* __restrict__ stats, unsigned* __restrict__ zero_words, int n_zero) {
+    int V, float c, int nseg, SegStat* __restrict__ stats, unsigned* __restrict__ zero_words, int n_zero,
+    const int32_t* __restrict__ q_row, int n_nodes) {
   const int seg = blockIdx.x;
   const int row = blockIdx.y;
   // side job of the first workgroup: clear the flags the walk kernel's workgroups exchange
@@ -39,7 +40,17 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
   const void* base = t_base;
   int dtype = t_dtype;
   int64_t r = row;
-  if (row >= n_t_rows) { base = q_base; dtype = q_dtype; r = row - n_t_rows; }
+  if (row >= n_t_rows) {
+    base = q_base; dtype = q_dtype; r = row - n_t_rows;
+    // With more draft rows than draft nodes (several drafters per position) most rows are nobody's:
+    // a row no node was drawn from (q_row, clamped as the walk clamps it) is not read at all.
+    if (q_row) {
+      int mine = 0;
+      for (int i = threadIdx.x; i < n_nodes; i += kStatThreads)
+        mine |= (min(max(q_row[i], 0), n_q_rows - 1) == static_cast<int>(r));
+      if (!__syncthreads_or(mine)) return;
+    }
+  }
   const int64_t row_off = r * static_cast<int64_t>(V);
   const int e_seg = seg * kStatSeg;
 
@@ -91,7 +102,7 @@ __global__ __launch_bounds__(kStatThreads) void zero_words_kernel(unsigned* __re
 
 void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void* q_base, int q_dtype,
                       int n_q_rows, int V, float c, SegStat* stats, hipStream_t stream, unsigned* zero_words,
-                      int n_zero) {
+                      int n_zero, const int32_t* q_row, int n_nodes) {
   const int rows = n_t_rows + n_q_rows;
   if (rows <= 0 || V <= 0) return;
   const int nseg = stats_segments(V);
@@ -99,10 +110,10 @@ void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void*
   const bool vec = (V % 8 == 0);
   if (vec)
     hipLaunchKernelGGL(row_stats_kernel<true>, grid, dim3(kStatThreads), 0, stream, t_base, t_dtype,
-                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero);
+                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero, q_row, n_nodes);
   else
     hipLaunchKernelGGL(row_stats_kernel<false>, grid, dim3(kStatThreads), 0, stream, t_base, t_dtype,
-                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero);
+                       n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero, q_row, n_nodes);
 }
 
 // ----------------------------------------------------------------------------------
@@ -698,8 +709,10 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   SegStat* stats = reinterpret_cast<SegStat*>(ws);
   unsigned* words = reinterpret_cast<unsigned*>(ws + lay.words_off);      // start of the zeroed region
   if (!a.target_stats_ready) {
+    // rows nobody was drawn from exist only when there are more draft rows than nodes
+    const bool sparse_q = n_q_stat_rows > a.total_nodes;
     launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream, words,
-                     static_cast<int>(lay.n_zero_words));
+                     static_cast<int>(lay.n_zero_words), sparse_q ? a.q_row : nullptr, a.total_nodes);
   } else if (n_q_stat_rows > 0) {
     // the target rows' entries were written by the LM-head kernel; only the draft rows are left
     launch_row_stats(a.draft_q, a.q_dtype, n_q_stat_rows, nullptr, 0, 0, a.V, c,

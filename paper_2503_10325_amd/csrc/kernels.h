@@ -13,7 +13,8 @@ struct AcceptParams;
 int stats_segments(int V);
 void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void* q_base, int q_dtype,
                       int n_q_rows, int V, float c, SegStat* stats, hipStream_t stream,
-                      unsigned* zero_words = nullptr, int n_zero = 0);
+                      unsigned* zero_words = nullptr, int n_zero = 0, const int32_t* q_row = nullptr,
+                      int n_nodes = 0);
 
 struct AcceptArgs {
   int B, V, total_nodes, n_q_rows;
