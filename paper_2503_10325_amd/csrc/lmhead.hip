@@ -248,16 +248,18 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
 // lane L holding hidden[32 tile + L % 32][64 slice + 32 (L / 32) + 8 j .. + 8]; rows past the end
 // are zero.
 //
-// A last row block with few rows costs more than its rows: each of its workgroups holds a CU while
-// it streams a whole weight tile for one or two row tiles of matrix work (the row count at which the
-// product is cheapest per row is a multiple of 512).
+// A last row block with few rows costs more than its rows: it needs one more pass over the weight
+// matrix (from the memory-side cache at best), so the row count at which the product is cheapest per
+// row is a multiple of 512.  Up to 32 remaining rows are handled by splitting the contraction over
+// the waves of the workgroup (below); more than that keeps the ordinary path with some waves idle.
 // ----------------------------------------------------------------------------------
 constexpr int kLwThreads = 512;
 constexpr int kLwRB = kLwThreads;                   // hidden rows per workgroup (64 per wave)
 constexpr int kLwStage = kLmVB * 8 / kLwThreads;     // 16-byte loads per thread and weight slice (128 rows x 8)
 constexpr int kLwStageRows = kLwThreads / 8;        // rows covered by one such load of the workgroup
 static_assert(kLwStage * kLwStageRows == kLmVB && kLwStage * kLwThreads * 16 == kLmVB * kLmKC * 2, "staging covers one weight slice exactly");
-constexpr int kLwLds = 2 * kLmHidBuf;               // two weight slices of 128 entries
+constexpr int kLwLds = 8 * kLmHidBuf;               // two shared weight slices; a partial last row block: one per wave
+static_assert(8 * 64 * 64 * 4 <= kLwLds, "the partial tiles of a split contraction fit");
 
 __global__ __launch_bounds__(256) void lm_pack_hidden_kernel(const uint16_t* __restrict__ hidden, int rows, int K,
                                                              int64_t n_items, lm_u32x4* __restrict__ packed) {
@@ -418,10 +420,81 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
       }
     }
   };
-  using Deep = std::integral_constant<int, 4>;
-  if (ntc == 2) slice_loop(std::integral_constant<int, 2>{}, std::integral_constant<int, PF2>{});
-  else if (ntc == 1) slice_loop(std::integral_constant<int, 1>{}, Deep{});
-  else slice_loop(std::integral_constant<int, 0>{}, Deep{});
+  // A row block of at most 32 rows (the remainder of rows / 512) would keep seven waves idle while
+  // the workgroup crawls through its 64 slices one load latency at a time.  Instead the eight waves
+  // split the contraction: wave w takes slices w, w + 8, ..., stages each in a weight buffer of its
+  // own (no workgroup barrier in the loop) and accumulates the same row tile; the eight partial
+  // tiles are then added through LDS into wave 0, which runs the ordinary epilogue.
+  const bool tail_block = __builtin_amdgcn_readfirstlane(P.rows - rbk * kLwRB) <= 32;     // the same in every wave
+  if (tail_block) {
+    unsigned char* mine = lm_lds + wave * kLmHidBuf;
+    const lm_u32x4* hs = packed + static_cast<int64_t>((rbk * kLwRB) >> 5) * nch * 256 + lane;
+    const int wrow = lane >> 3, wseg = lane & 7;
+    lm_u32x4 wl[16];
+    auto issue = [&](int c) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        int vrow = v0 + wrow + 8 * j;
+        vrow = vrow < P.V ? vrow : P.V - 1;
+        wl[j] = *reinterpret_cast<const lm_u32x4*>(P.weight + static_cast<int64_t>(vrow) * P.K + c * kLmKC + wseg * 8);
+      }
+    };
+    // slices of this wave: wave, wave + 8, ...; a wave without slices (d_model < 512) loads slice 0 and
+    // multiplies nothing.  (Two slices in flight per wave were no faster: what the remainder costs is
+    // one more pass over the weights.)
+    const int n_mine = wave < nch ? (nch - wave + 7) / 8 : 0;
+    issue(wave < nch ? wave : 0);
+    for (int i = 0; i < n_mine; ++i) {
+      const int c = wave + 8 * i;
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        *reinterpret_cast<lm_u32x4*>(mine + (wrow + 8 * j) * kLmPitch + wseg * 16) = wl[j];
+      lm_u32x4 b[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = hs[(c * 4 + j) * 64];
+      issue(c + 8 < nch ? c + 8 : c);                   // unconditional: the last one repeats this slice
+      const unsigned char* wrd = mine + ln * kLmPitch + lh * 64;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+          const lm_u32x4 a = *reinterpret_cast<const lm_u32x4*>(wrd + mi * 32 * kLmPitch + 16 * j);
+          acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a),
+                                                               __builtin_bit_cast(lm_bf16x8, b[j]), acc[mi][0], 0, 0, 0);
+        }
+      }
+    }
+    // add the eight partial tiles: 64 floats per lane and wave, 16 KB each
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(lm_lds) + wave * (64 * 64);
+    if (wave > 0) {
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[(mi * 16 + r) * 64 + lane] = acc[mi][0][r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+      for (int w = 1; w < kLwThreads / 64; ++w) {
+        const float* rw = reinterpret_cast<const float*>(lm_lds) + w * (64 * 64);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[mi][0][r] += rw[(mi * 16 + r) * 64 + lane];
+      }
+    } else {
+      // the other waves hold partial sums of wave 0's rows, not tiles of their own
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mi][0][r] = 0.f;
+    }
+  } else {
+    using Deep = std::integral_constant<int, 4>;
+    if (ntc == 2) slice_loop(std::integral_constant<int, 2>{}, std::integral_constant<int, PF2>{});
+    else if (ntc == 1) slice_loop(std::integral_constant<int, 1>{}, Deep{});
+    else slice_loop(std::integral_constant<int, 0>{}, Deep{});
+  }
 
   // each wave holds all 128 vocabulary entries of the block for its rows: statistics need no LDS
   const bool vec4 = (P.V & 3) == 0;
@@ -517,6 +590,11 @@ int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kLmLds) != hipSuccess)
+      return -1;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_wide_kernel<2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLwLds) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_wide_kernel<4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLwLds) != hipSuccess)
       return -1;
     attr_set = true;
   }
