@@ -42,13 +42,25 @@ def compare_accept(gpu: dict, ref: dict, n: np.ndarray):
     return bad, ties, B
 
 
+def visited_pattern_agrees(gpu: dict, ref: dict, node_offsets: np.ndarray) -> bool:
+    """The GPU visited (wrote a ratio for) exactly the nodes the oracle visited, in every request
+    the oracle did not flag as a near-tie (after a near-tie the two walks may part ways)."""
+    for b in range(ref["accept_len"].shape[0]):
+        if ref["near_tie"][b]:
+            continue
+        o, e = int(node_offsets[b]), int(node_offsets[b + 1])
+        if not np.array_equal(np.isnan(gpu["ratio"][o:e]), np.isnan(ref["ratio"][o:e])):
+            return False
+    return True
+
+
 def ratio_err(gpu_ratio: np.ndarray, ref_ratio: np.ndarray) -> float:
-    """Largest relative deviation of the compared ratios on nodes the oracle visited."""
+    """Largest relative deviation of the compared ratios on nodes both walks visited (that the
+    two visit the same nodes is checked by visited_pattern_agrees)."""
     vis = ~np.isnan(ref_ratio)
-    assert np.array_equal(np.isnan(gpu_ratio), ~vis) or True
     r = ref_ratio[vis]
     g = gpu_ratio[vis].astype(np.float64)
-    fin = np.isfinite(r) & (r > 0)
+    fin = np.isfinite(r) & (r > 0) & ~np.isnan(g)
     if not fin.any():
         return 0.0
     return float(np.max(np.abs(g[fin] - r[fin]) / r[fin]))
