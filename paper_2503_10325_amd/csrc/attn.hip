@@ -69,16 +69,6 @@ struct AttnParams {
   int out_f32;
 };
 
-#ifdef SPECV_PROFILE
-// Development-only cycle accounting of the token-split kernel (never part of a normal build).
-__device__ unsigned long long g_prof[8];
-#define PROF_T() clock64()
-#define PROF_ADD(i, v) do { if (lane == 0) atomicAdd(&g_prof[i], static_cast<unsigned long long>(v)); } while (0)
-#else
-#define PROF_T() 0ll
-#define PROF_ADD(i, v) do { } while (0)
-#endif
-
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -292,8 +282,6 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
     }
   };
 
-  const long long prof_t0 = PROF_T();
-  long long prof_store = 0, prof_compute = 0, prof_tiles = 0, prof_qk = 0, prof_sm = 0;
   int t = my_slice;
   if (wave_active && t < ntiles) {
     fetch_pages(t);
@@ -301,7 +289,6 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
     fetch_pages(t + nslice);
   }
   for (; wave_active && t < ntiles; t += nslice) {
-    const long long prof_a = PROF_T();
     // ---- registers -> LDS ----
 #pragma unroll
     for (int j = 0; j < C::kLoads; ++j) {
@@ -340,7 +327,6 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
       fetch_pages(t + 2 * nslice);
     }
     wave_lds_fence();
-    const long long prof_b = PROF_T();
 
     // ---- S^T = K Q^T ----
     f32x16 sacc;
@@ -352,7 +338,6 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
     }
 
-    const long long prof_q = PROF_T();
     // ---- mask, online softmax ----
     const bool need_mask = tok0 + kTile > ctx;
     float tmax = -INFINITY;
@@ -379,7 +364,6 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
-    const long long prof_s = PROF_T();
     // ---- P^T as two bf16 terms (value + rounding residual), 16 tokens at a time; O^T += V^T P^T ----
     // A single bf16 rounding of P (2^-9 relative) would dominate the output error; carrying the
     // rounding residual in a second bf16 term keeps ~16 bits of every weight.
@@ -409,14 +393,7 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
     l_run = l_run * alpha + psum;
     m_run = m_new;
     wave_lds_fence();
-    const long long prof_c = PROF_T();
-    prof_store += prof_b - prof_a;
-    prof_compute += prof_c - prof_b;
-    prof_qk += prof_q - prof_b;
-    prof_sm += prof_s - prof_q;
-    prof_tiles += 1;
   }
-  const long long prof_t1 = PROF_T();
 
   // ---- merge the waves that share a query block ----
   l_run = half_sum(l_run);
@@ -489,15 +466,6 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
       if ((tid & 7) == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(Mq, Ls);
     }
   }
-  PROF_ADD(0, 1);
-  PROF_ADD(1, prof_t1 - prof_t0);
-  PROF_ADD(2, prof_store);
-  PROF_ADD(3, prof_compute);
-  PROF_ADD(4, prof_tiles);
-  PROF_ADD(5, PROF_T() - prof_t1);
-  PROF_ADD(6, prof_qk);
-  PROF_ADD(7, prof_sm);
-  (void)prof_t0; (void)prof_t1; (void)prof_store; (void)prof_compute; (void)prof_tiles;
 }
 
 // Grid-mapped launch: blockIdx = (chunk + max_chunks * row group, KV head, request); workgroups
@@ -1136,14 +1104,3 @@ int launch_attn(const AttnArgs& a, hipStream_t stream) {
 }
 
 }  // namespace specv
-
-#ifdef SPECV_PROFILE
-extern "C" void spec_debug_read_prof(unsigned long long* out8, int reset) {
-  (void)hipMemcpyFromSymbol(out8, HIP_SYMBOL(specv::g_prof), 8 * sizeof(unsigned long long));
-  if (reset) {
-    unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    (void)hipMemcpyToSymbol(HIP_SYMBOL(specv::g_prof), z, sizeof z);
-  }
-}
-#endif
-

@@ -282,7 +282,7 @@ def test_lm_head_full_size_rows_and_columns(rt, rows, d_model, V):
     rng = np.random.default_rng(11)
     border = [0, 31, 32, 63, 64, 127, 128, 255, 256, 257, 511, 512, 513, 543, 544, 1023, 1024, 1039,
               rows - 33, rows - 32, rows - 17, rows - 16, rows - 2, rows - 1]
-    rsel = sorted(set([r for r in border if 0 <= r < rows] + rng.integers(0, rows, size=16).tolist()))
+    rsel = sorted(set([r for r in border if 0 <= r < rows] + rng.integers(0, rows, size=32).tolist()))
     assert len(rsel) >= 32
     vborder = [0, 1, 31, 32, 127, 128, 8191, 8192, 65535, 65536, V - 257, V - 256, V - 129, V - 128, V - 2, V - 1]
     vsel = sorted(set(vborder + rng.integers(0, V, size=520).tolist()))[:512 + len(vborder)]
