@@ -20,6 +20,8 @@
  *   - Calls validate their host-visible arguments, enqueue kernels on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and return without
  *     synchronising.  Outputs are valid once the stream has been synchronised.
+ *   - The library keeps no state between calls and reads no environment variable; every
+ *     launch decision is a function of the call's arguments and of the current device.
  *   - Return value: SPEC_OK (0) or a negative spec_status.  Nothing is enqueued when
  *     validation fails.  Data that lives on the device (parent[], block_table[],
  *     token ids) is NOT validated: out-of-range page or token indices are undefined
@@ -96,6 +98,11 @@ int32_t spec_verify_attn(
     float* lse,                  /* optional [total_q, Hq]: natural-log sum-exp of the
                                     scaled scores over the allowed set; may be NULL    */
     void* workspace, size_t workspace_bytes, void* stream);
+/* q, k_pool, v_pool and out must be 16-byte aligned (SPEC_ERR_SHAPE otherwise). */
+
+/* Writes a one-line description of the kernels and the context split that spec_verify_attn uses
+ * for this descriptor into buf (host; for logs and benchmark reports). */
+int32_t spec_describe_attn_plan(const spec_attn_desc* desc, char* buf, size_t buf_bytes);
 
 /* ------------------------------------------------------------------------------
  * spec_fuse_drafts
@@ -177,6 +184,37 @@ int32_t spec_accept(
     float* dbg_ratio,            /* optional [total_nodes]: ratio compared at each visited
                                     node, NaN where not visited                         */
     void* workspace, size_t workspace_bytes, void* stream);
+
+/* spec_accept with explicit launch choices, for tests and sweeps (same arguments, same results).
+ * With bf16 logit rows (16-byte aligned, V a multiple of 8) and a batch of at most one request per
+ * compute unit, spec_accept walks every request with a cluster of workgroups that keep the rows
+ * of the walked path in registers and read no other row (path 2); other inputs take a statistics
+ * pass over all rows followed by one walking workgroup per request (path 1).  No wait between
+ * workgroups is unbounded: `patience` is the number of polls one spends waiting for its peers
+ * before it does their share itself (0 = never wait).  tuning == NULL is spec_accept. */
+typedef struct {
+  int32_t path;      /* 0 = library's choice, 1 = statistics pass + walk, 2 = workgroup clusters (falls
+                        back to 1 when the inputs do not qualify)                                  */
+  int32_t levels;    /* path 2: rows of the walk looked at in one exchange, 0 = library's choice   */
+  int32_t slices;    /* path 2: workgroups one row pair is cut over, 0 = library's choice          */
+  int32_t patience;  /* < 0 = library's choice                                                     */
+  int32_t helpers;   /* path 1: helper workgroups per request (0..3), < 0 = library's choice       */
+} spec_accept_tuning;
+
+int32_t spec_accept_tuned(
+    const spec_accept_tuning* tuning, /* host, may be NULL                                 */
+    int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
+    const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+    const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
+    int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
+    const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
+    int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream);
+
+/* One-line description of what spec_accept launches for this shape on the current device
+ * (host; for logs and benchmark reports). */
+int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V,
+                                  int32_t max_nodes_per_req, int32_t is_tree, int32_t target_dtype,
+                                  int32_t q_dtype, int32_t q_kind, char* buf, size_t buf_bytes);
 
 /* ------------------------------------------------------------------------------
  * spec_accept_greedy

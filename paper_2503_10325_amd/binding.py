@@ -21,7 +21,8 @@ SPEC_Q_LOGITS, SPEC_Q_PROBS = 0, 1
 EXPORTS = [
     "spec_verify_attn_workspace_size", "spec_verify_attn",
     "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
-    "spec_accept_workspace_size", "spec_accept",
+    "spec_accept_workspace_size", "spec_accept", "spec_accept_tuned",
+    "spec_describe_attn_plan", "spec_describe_accept_plan",
     "spec_accept_greedy_workspace_size", "spec_accept_greedy",
     "spec_routing_scores", "spec_adaptive_speculation", "spec_compact_kv",
     "spec_row_stats_size", "spec_lm_head_workspace_size", "spec_lm_head", "spec_accept_prestats",
@@ -36,6 +37,15 @@ class SpecAttnDesc(ctypes.Structure):
         ("max_q_per_req", ctypes.c_int32), ("max_pages_per_req", ctypes.c_int32),
         ("total_kv_tokens_hint", ctypes.c_int64), ("scale", ctypes.c_float), ("out_dtype", ctypes.c_int32),
     ]
+
+
+class SpecAcceptTuning(ctypes.Structure):
+    """Explicit launch choices of spec_accept_tuned (0 / negative = the library's choice)."""
+    _fields_ = [("path", ctypes.c_int32), ("levels", ctypes.c_int32), ("slices", ctypes.c_int32),
+                ("patience", ctypes.c_int32), ("helpers", ctypes.c_int32)]
+
+    def __init__(self, path=0, levels=0, slices=0, patience=-1, helpers=-1):
+        super().__init__(path, levels, slices, patience, helpers)
 
 
 class SpecError(RuntimeError):
@@ -83,6 +93,12 @@ def lib() -> ctypes.CDLL:
                                   + [vp] * 3 + [sz, vp])
         L.spec_accept_prestats.restype = i32
         L.spec_accept_prestats.argtypes = L.spec_accept.argtypes
+        L.spec_accept_tuned.restype = i32
+        L.spec_accept_tuned.argtypes = [ctypes.POINTER(SpecAcceptTuning)] + L.spec_accept.argtypes
+        L.spec_describe_attn_plan.restype = i32
+        L.spec_describe_attn_plan.argtypes = [ctypes.POINTER(SpecAttnDesc), ctypes.c_char_p, sz]
+        L.spec_describe_accept_plan.restype = i32
+        L.spec_describe_accept_plan.argtypes = [ctypes.POINTER(SpecAcceptTuning)] + [i32] * 7 + [ctypes.c_char_p, sz]
         L.spec_row_stats_size.restype = sz
         L.spec_row_stats_size.argtypes = [i32, i32]
         L.spec_lm_head_workspace_size.restype = sz
@@ -183,6 +199,42 @@ def spec_accept(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_t
                            _ptr(workspace), ws_bytes, _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_accept", rc)
+
+
+def spec_accept_tuned(tuning, B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_tokens, target_logits,
+                      draft_q, q_kind, q_row, temperature, u_accept, u_resample, accept_len, out_tokens,
+                      stop_node=None, dbg_ratio=None, workspace=None, stream=None) -> None:
+    """spec_accept with explicit launch choices (a SpecAcceptTuning or None)."""
+    V = target_logits.shape[1]
+    n_q_rows = 0 if draft_q is None else draft_q.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().spec_accept_tuned(None if tuning is None else ctypes.byref(tuning), B, V, total_nodes, n_q_rows,
+                                 max_nodes_per_req, _ptr(node_offsets), _ptr(parent), _ptr(draft_tokens),
+                                 _ptr(target_logits), _dtype_code(target_logits), _ptr(draft_q),
+                                 SPEC_BF16 if draft_q is None else _dtype_code(draft_q), int(q_kind), _ptr(q_row),
+                                 float(temperature), _ptr(u_accept), _ptr(u_resample), _ptr(accept_len),
+                                 _ptr(out_tokens), out_tokens.shape[1], _ptr(stop_node), _ptr(dbg_ratio),
+                                 _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_accept_tuned", rc)
+
+
+def spec_describe_attn_plan(desc: SpecAttnDesc) -> str:
+    buf = ctypes.create_string_buffer(512)
+    rc = lib().spec_describe_attn_plan(ctypes.byref(desc), buf, 512)
+    if rc != SPEC_OK:
+        raise SpecError("spec_describe_attn_plan", rc)
+    return buf.value.decode()
+
+
+def spec_describe_accept_plan(B, V, max_nodes_per_req, is_tree, target_dtype=SPEC_BF16, q_dtype=SPEC_BF16,
+                              q_kind=SPEC_Q_LOGITS, tuning=None) -> str:
+    buf = ctypes.create_string_buffer(512)
+    rc = lib().spec_describe_accept_plan(None if tuning is None else ctypes.byref(tuning), B, V, max_nodes_per_req,
+                                         int(bool(is_tree)), target_dtype, q_dtype, q_kind, buf, 512)
+    if rc != SPEC_OK:
+        raise SpecError("spec_describe_accept_plan", rc)
+    return buf.value.decode()
 
 
 def spec_accept_prestats(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_tokens, target_logits,

@@ -10,8 +10,6 @@
 //                       pass over a row pair (residual mass, inverse-CDF search) is
 //                       spread over the workgroup's 16 waves and, for large vocabularies,
 //                       over the waves of up to three helper workgroups.
-#include <stdlib.h>
-
 #include "common.h"
 #include "kernels.h"
 
@@ -107,7 +105,7 @@ void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void*
   if (rows <= 0 || V <= 0) return;
   const int nseg = stats_segments(V);
   dim3 grid(nseg, rows);
-  const bool vec = (V % 8 == 0);
+  const bool vec = (V % 8 == 0) && aligned16(t_base) && aligned16(q_base);
   if (vec)
     hipLaunchKernelGGL(row_stats_kernel<true>, grid, dim3(kStatThreads), 0, stream, t_base, t_dtype,
                        n_t_rows, q_base, q_dtype, n_q_rows, V, c, nseg, stats, zero_words, n_zero, q_row, n_nodes);
@@ -268,7 +266,8 @@ __device__ __forceinline__ PartSlot ld_slot(const PartSlot* p) {
   return r;
 }
 constexpr unsigned kDone = 0xffffffffu;    // pass number that tells the helpers to leave
-constexpr int kSpinLimit = 4000000;        // a helper whose master never shows up leaves after this many polls (seconds)
+constexpr int kSpinLimit = 4000;           // a helper whose master never shows up leaves after this many polls (a few
+                                           // milliseconds: ten times the master's own patience)
 
 struct PassDesc {            // written by the master, published by `seq` (pass number, from 1)
   unsigned seq;
@@ -680,7 +679,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
 // Workspace: [row statistics][helper protocol: pass descriptors, hand-back slots (zeroed by the
 // statistics kernel)]
 struct AcceptLayout {
-  size_t words_off, n_zero_words, desc_off, part_off, total;
+  size_t words_off, n_zero_words, desc_off, part_off, msg_off, total;
 };
 
 static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
@@ -690,13 +689,25 @@ static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
   l.words_off = up(rows * stats_segments(V) * sizeof(SegStat));
   l.desc_off = l.words_off;
   l.part_off = l.desc_off + up(static_cast<size_t>(B) * sizeof(PassDesc));
-  l.total = l.part_off + up(static_cast<size_t>(B) * kMaxHelpers * kWalkWaves * sizeof(PartSlot)) + 256;
-  l.n_zero_words = (l.total - 256 - l.words_off) / sizeof(unsigned);     // flags, descriptors and hand-back slots
+  l.msg_off = l.part_off + up(static_cast<size_t>(B) * kMaxHelpers * kWalkWaves * sizeof(PartSlot));
+  l.n_zero_words = (l.msg_off - l.words_off) / sizeof(unsigned);         // flags, descriptors and hand-back slots
+  l.total = l.msg_off + up(cluster_msg_bytes(B)) + 256;                  // messages of the cluster path
   return l;
 }
 
 size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V) {
   return accept_layout(B, total_nodes, n_q_rows, V).total;
+}
+
+const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
+  const bool vec = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
+  const bool cluster_ok = vec && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
+                          a.q_kind == 0 && !a.target_stats_ready;
+  const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && a.B <= n_cu));
+  if (!cluster) return "row_stats_kernel (all rows) + accept_walk_kernel (one workgroup per request, helper workgroups)";
+  const ClusterPlan p = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
+  return p.solo ? "accept_cluster_kernel (one workgroup per request, rows of the walked path only)"
+                : "accept_cluster_kernel (cluster of workgroups per request, register-resident row slices)";
 }
 
 void launch_accept(const AcceptArgs& a, hipStream_t stream) {
@@ -706,6 +717,18 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   const int n_q_stat_rows = (a.q_kind == 0) ? a.n_q_rows : 0;
   const AcceptLayout lay = accept_layout(a.B, a.total_nodes, a.n_q_rows, a.V);
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+  const int n_cu = current_device_cus();
+  {
+    // bf16 logit rows (the default layout): one kernel that reads only the rows the walk reaches
+    const bool vec0 = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
+    const bool cluster_ok = vec0 && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
+                            a.q_kind == 0 && !a.target_stats_ready;
+    if (cluster_ok && (a.path == 2 || (a.path == 0 && a.B <= n_cu))) {
+      const ClusterPlan plan = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
+      launch_accept_cluster(a, plan, a.patience >= 0 ? a.patience : 4000, ws + lay.msg_off, stream);
+      return;
+    }
+  }
   SegStat* stats = reinterpret_cast<SegStat*>(ws);
   unsigned* words = reinterpret_cast<unsigned*>(ws + lay.words_off);      // start of the zeroed region
   if (!a.target_stats_ready) {
@@ -734,30 +757,16 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   P.part = reinterpret_cast<PartSlot*>(ws + lay.part_off);
   // Helpers pay when a pass is long against a hand-off between compute units (a few microseconds):
   // vocabularies of 64k classes and more; masters plus helpers stay within one workgroup per compute unit.
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
-      n_cu = 256;
-  }
   int helpers = 0;
   if (a.V >= 65536) {
     helpers = n_cu / a.B - 1;
     helpers = helpers < 0 ? 0 : (helpers > kMaxHelpers ? kMaxHelpers : helpers);
   }
-  if (const char* e = getenv("SPECV_WALK_HELPERS")) {       // development knob
-    const int v = atoi(e);
-    if (v >= 0 && v <= kMaxHelpers && a.B * (1 + v) <= n_cu) helpers = v;
-  }
+  if (a.helpers >= 0 && a.helpers <= kMaxHelpers && a.B * (1 + a.helpers) <= n_cu) helpers = a.helpers;   // per-call tuning
   P.helpers = helpers;
-  P.patience = 400;                                          // a few hundred microseconds
-  if (const char* e = getenv("SPECV_WALK_PATIENCE")) {      // development knob: 0 makes every pass fall back
-    const int v = atoi(e);
-    if (v >= 0 && v <= 1000000) P.patience = v;
-  }
+  P.patience = (a.patience >= 0 && a.patience <= 1000000) ? a.patience : 400;   // default: a few hundred microseconds
   const dim3 grid(a.B * (1 + helpers));
-  const bool vec = (a.V % 8 == 0);
+  const bool vec = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
   const bool fast = vec && a.V >= 8 && a.t_dtype == kBF16 && a.q_dtype == kBF16 && a.q_kind == 0;
   if (fast) hipLaunchKernelGGL((accept_walk_kernel<true, true>), grid, dim3(kWalkThreads), 0, stream, P);
   else if (vec) hipLaunchKernelGGL((accept_walk_kernel<true, false>), grid, dim3(kWalkThreads), 0, stream, P);

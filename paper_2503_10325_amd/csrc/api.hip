@@ -1,6 +1,8 @@
 // C ABI of the verification library: argument validation and dispatch only.
 #include "../../include/spec_verify.h"
 
+#include <stdio.h>
+
 #include "kernels.h"
 
 using namespace specv;
@@ -19,7 +21,7 @@ const char* spec_strerror(int32_t status) {
   }
 }
 
-int32_t spec_abi_version(void) { return 1; }
+int32_t spec_abi_version(void) { return 2; }
 
 static int check_attn_desc(const spec_attn_desc* d) {
   if (!d) return SPEC_ERR_NULL;
@@ -49,7 +51,8 @@ static AttnArgs attn_args_from(const spec_attn_desc* d) {
 
 size_t spec_verify_attn_workspace_size(const spec_attn_desc* desc) {
   if (check_attn_desc(desc) != SPEC_OK) return 0;
-  return attn_workspace_bytes(attn_args_from(desc));
+  const AttnArgs a = attn_args_from(desc);
+  return attn_workspace_bytes(a, make_attn_plan(a));
 }
 
 int32_t spec_verify_attn(const spec_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
@@ -60,13 +63,29 @@ int32_t spec_verify_attn(const spec_attn_desc* desc, const void* q, const void* 
   if (rc != SPEC_OK) return rc;
   if (desc->batch == 0 || desc->total_q == 0) return SPEC_OK;
   if (!q || !k_pool || !v_pool || !block_table || !ctx_len || !q_offsets || !out) return SPEC_ERR_NULL;
+  // the kernels read q and the pools and write out with 16-byte accesses
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
+       reinterpret_cast<uintptr_t>(out)) & 15u)
+    return SPEC_ERR_SHAPE;
   AttnArgs a = attn_args_from(desc);
   if (a.scale == 0.f) a.scale = 1.0f / sqrtf(static_cast<float>(a.D));
-  const size_t need = attn_workspace_bytes(a);
+  const AttnPlan plan = make_attn_plan(a);
+  const size_t need = attn_workspace_bytes(a, plan);
   if (need > 256 && (!workspace || workspace_bytes < need)) return SPEC_ERR_WORKSPACE;
   a.q = q; a.k_pool = k_pool; a.v_pool = v_pool; a.block_table = block_table; a.ctx_len = ctx_len;
   a.q_offsets = q_offsets; a.parent = parent; a.out = out; a.lse = lse; a.workspace = workspace;
-  return launch_attn(a, static_cast<hipStream_t>(stream));
+  return launch_attn(a, plan, static_cast<hipStream_t>(stream));
+}
+
+int32_t spec_describe_attn_plan(const spec_attn_desc* desc, char* buf, size_t buf_bytes) {
+  const int rc = check_attn_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (!buf || buf_bytes == 0) return SPEC_ERR_NULL;
+  const AttnArgs a = attn_args_from(desc);
+  const AttnPlan p = make_attn_plan(a);
+  snprintf(buf, buf_bytes, "%s; head_dim %d; context chunks of %d tokens, at most %d per request", attn_plan_name(p),
+           a.D, p.chunk_tokens, p.max_chunks);
+  return SPEC_OK;
 }
 
 size_t spec_fuse_drafts_workspace_size(int32_t B, int32_t k_max, int32_t N, int32_t V, int32_t mode) {
@@ -105,7 +124,7 @@ size_t spec_accept_workspace_size(int32_t B, int32_t total_nodes, int32_t n_q_ro
   return accept_workspace_bytes(B, total_nodes, n_q_rows, V);
 }
 
-static int32_t accept_entry(bool prestats, int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
+static int32_t accept_entry(bool prestats, const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
                             int32_t max_nodes_per_req, const int32_t* node_offsets, const int32_t* parent,
                             const int32_t* draft_tokens, const void* target_logits, int32_t target_dtype,
                             const void* draft_q, int32_t q_dtype, int32_t q_kind, const int32_t* q_row,
@@ -134,6 +153,13 @@ static int32_t accept_entry(bool prestats, int32_t B, int32_t V, int32_t total_n
   a.u_accept = u_accept; a.u_resample = u_resample; a.accept_len = accept_len; a.out_tokens = out_tokens;
   a.out_stride = out_stride; a.stop_node = stop_node; a.dbg_ratio = dbg_ratio; a.workspace = workspace;
   a.target_stats_ready = prestats;
+  a.max_nodes = max_nodes_per_req;
+  a.path = 0; a.levels = 0; a.slices = 0; a.patience = -1; a.helpers = -1;
+  if (tuning) {
+    if (tuning->path < 0 || tuning->path > 2 || tuning->levels < 0 || tuning->slices < 0) return SPEC_ERR_SHAPE;
+    a.path = tuning->path; a.levels = tuning->levels; a.slices = tuning->slices;
+    a.patience = tuning->patience; a.helpers = tuning->helpers;
+  }
   launch_accept(a, static_cast<hipStream_t>(stream));
   return hipGetLastError() == hipSuccess ? SPEC_OK : SPEC_ERR_LAUNCH;
 }
@@ -145,10 +171,42 @@ int32_t spec_accept(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
                     const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
                     int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes,
                     void* stream) {
-  return accept_entry(false, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent, draft_tokens,
+  return accept_entry(false, nullptr, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent, draft_tokens,
                       target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature, u_accept,
                       u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, workspace,
                       workspace_bytes, stream);
+}
+
+int32_t spec_accept_tuned(const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t total_nodes,
+                          int32_t n_q_rows, int32_t max_nodes_per_req, const int32_t* node_offsets,
+                          const int32_t* parent, const int32_t* draft_tokens, const void* target_logits,
+                          int32_t target_dtype, const void* draft_q, int32_t q_dtype, int32_t q_kind,
+                          const int32_t* q_row, float temperature, const float* u_accept, const float* u_resample,
+                          int32_t* accept_len, int32_t* out_tokens, int32_t out_stride, int32_t* stop_node,
+                          float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream) {
+  return accept_entry(false, tuning, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent,
+                      draft_tokens, target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature,
+                      u_accept, u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, workspace,
+                      workspace_bytes, stream);
+}
+
+int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t max_nodes_per_req,
+                                  int32_t is_tree, int32_t target_dtype, int32_t q_dtype, int32_t q_kind,
+                                  char* buf, size_t buf_bytes) {
+  if (B < 0 || V <= 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
+  if (!buf || buf_bytes == 0) return SPEC_ERR_NULL;
+  AcceptArgs a{};
+  a.B = B; a.V = V; a.max_nodes = max_nodes_per_req; a.t_dtype = target_dtype; a.q_dtype = q_dtype; a.q_kind = q_kind;
+  static const int32_t some_parent = 0;
+  a.parent = is_tree ? &some_parent : nullptr;       // only its being NULL or not matters to the plan
+  a.patience = -1; a.helpers = -1;
+  if (tuning) { a.path = tuning->path; a.levels = tuning->levels; a.slices = tuning->slices; }
+  const int n_cu = current_device_cus();
+  const char* name = accept_plan_name(a, n_cu);
+  const ClusterPlan p = make_cluster_plan(B, V, max_nodes_per_req, is_tree != 0, n_cu, a.levels, a.slices);
+  snprintf(buf, buf_bytes, "%s; cluster plan for this shape: %d level(s) x %d slice(s) of %d logits%s", name,
+           p.solo ? 1 : p.levels, p.slices, p.upt * 8192, p.solo ? " (one workgroup)" : "");
+  return SPEC_OK;
 }
 
 int32_t spec_accept_prestats(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows,
@@ -159,7 +217,7 @@ int32_t spec_accept_prestats(int32_t B, int32_t V, int32_t total_nodes, int32_t 
                              int32_t* accept_len, int32_t* out_tokens, int32_t out_stride, int32_t* stop_node,
                              float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream) {
   if (target_dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
-  return accept_entry(true, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent, draft_tokens,
+  return accept_entry(true, nullptr, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent, draft_tokens,
                       target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature, u_accept,
                       u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, workspace,
                       workspace_bytes, stream);

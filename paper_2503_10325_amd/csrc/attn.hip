@@ -939,18 +939,20 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P) {
 // ----------------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------------
-struct AttnPlan {
-  int kind;           // 0: token-split kernel (<= 128 rows per KV head), 1: row-split, 4 waves, 2: row-split, 8 waves
-  int rows_per_wg;
-  int row_groups;
-  int chunk_tokens;
-  int max_chunks;
-  int tau;            // > 0: sorted-work-list launch of the token-split kernel, at most tau tiles per wave and item
-};
-
 constexpr int kListMaxChunks = 16;
 
-static AttnPlan make_plan(const AttnArgs& a) {
+// Development knobs for sweeps, compiled in only with -DSPECV_DEV_KNOBS (normal builds read no
+// environment variable and keep no state between calls).
+#ifdef SPECV_DEV_KNOBS
+static long dev_knob(const char* name, long fallback) {
+  const char* e = getenv(name);
+  return e ? atol(e) : fallback;
+}
+#else
+static long dev_knob(const char*, long fallback) { return fallback; }
+#endif
+
+AttnPlan make_attn_plan(const AttnArgs& a) {
   AttnPlan p;
   p.tau = 0;
   const int G = a.Hq / a.Hkv;
@@ -958,12 +960,10 @@ static AttnPlan make_plan(const AttnArgs& a) {
   if (max_rows <= 128) { p.kind = 0; p.rows_per_wg = 128; }
   else if (a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
   else { p.kind = 2; p.rows_per_wg = 256; }
-  if (const char* e = getenv("SPECV_ATTN_KIND")) {      // development knob: force a kernel family
-    const int k = atoi(e);
-    if (k == 1) { p.kind = 1; p.rows_per_wg = 128; }
-    if (k == 2 && a.D == 128) { p.kind = 2; p.rows_per_wg = 256; }
-    if (k == 0) { p.kind = 0; p.rows_per_wg = 128; }
-  }
+  const long force_kind = dev_knob("SPECV_ATTN_KIND", -1);            // force a kernel family
+  if (force_kind == 1) { p.kind = 1; p.rows_per_wg = 128; }
+  if (force_kind == 2 && a.D == 128) { p.kind = 2; p.rows_per_wg = 256; }
+  if (force_kind == 0) { p.kind = 0; p.rows_per_wg = 128; }
   p.row_groups = (max_rows + p.rows_per_wg - 1) / p.rows_per_wg;
   const bool token_split = (p.kind == 0);
   const int gran = token_split ? kTile : 64;              // chunks are whole tiles
@@ -973,13 +973,10 @@ static AttnPlan make_plan(const AttnArgs& a) {
   // partial-result round trip proportional to its query rows), so chunks are as long as two
   // limits allow: (a) about one workgroup per compute unit should exist, (b) one wave should not
   // stream more than ~40 tiles in sequence, or the longest workgroup sets the kernel's duration.
-  int64_t jobs_target = 256;
-  if (const char* e = getenv("SPECV_ATTN_JOBS")) {      // development knob for sweeps
-    const long v = atol(e);
-    if (v > 0) jobs_target = v;
-  }
+  const long jobs_knob = dev_knob("SPECV_ATTN_JOBS", 0);
+  const int64_t jobs_target = jobs_knob > 0 ? jobs_knob : 256;
   int64_t chunk = (tok * a.Hkv * p.row_groups + jobs_target - 1) / jobs_target;
-  if (token_split && !getenv("SPECV_ATTN_JOBS")) {
+  if (token_split && jobs_knob <= 0) {
     // waves that share one query block (pair) and therefore split its tiles
     const int nslice = max_rows <= 32 ? 4 : (max_rows <= 64 ? 2 : 1);
     const int64_t cap = static_cast<int64_t>(40) * kTile * nslice;
@@ -1000,11 +997,9 @@ static AttnPlan make_plan(const AttnArgs& a) {
   // request says whether they do.
   const bool ragged = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok;
   int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 36 : 0;
-  if (const char* e = getenv("SPECV_ATTN_TAU")) {         // development knob for sweeps (0: grid-mapped launch)
-    const int v = atoi(e);
-    if (token_split && a.B <= kPlanMaxB && v >= 0 && v <= 255) tau = v;
-  }
-  if (getenv("SPECV_ATTN_JOBS")) tau = 0;
+  const long tau_knob = dev_knob("SPECV_ATTN_TAU", -1);   // 0: grid-mapped launch
+  if (token_split && a.B <= kPlanMaxB && tau_knob >= 0 && tau_knob <= 255) tau = static_cast<int>(tau_knob);
+  if (jobs_knob > 0) tau = 0;
   if (tau > 0) {
     // most tiles one wave can have to stream: the longest request, shared by as many waves as the
     // largest declared row count leaves per query block (requests with fewer rows get more waves)
@@ -1017,22 +1012,16 @@ static AttnPlan make_plan(const AttnArgs& a) {
   return p;
 }
 
-size_t attn_workspace_bytes(const AttnArgs& a) {
-  const AttnPlan p = make_plan(a);
+size_t attn_workspace_bytes(const AttnArgs& a, const AttnPlan& p) {
   if (p.max_chunks <= 1) return 256;
   const size_t rows = static_cast<size_t>(a.total_q) * a.Hq;
   return rows * p.max_chunks * (a.D + 2) * sizeof(float) + 256;
 }
 
-template <typename K>
-static int set_lds_once(K kernel, size_t lds, bool& done) {
-  if (!done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(lds)) != hipSuccess)
-      return -6;
-    done = true;
-  }
-  return 0;
+const char* attn_plan_name(const AttnPlan& p) {
+  if (p.kind == 0) return p.tau > 0 ? "attn_stream_list_kernel (token-split body, device-built work list sorted by length)"
+                                    : "attn_stream_kernel (token-split body, one workgroup per request x KV head x context chunk)";
+  return p.kind == 1 ? "attn_rows_kernel<4 waves> (row-split body)" : "attn_rows_kernel<8 waves> (row-split body)";
 }
 
 template <int D>
@@ -1041,18 +1030,12 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
   constexpr size_t kMerge = kAttnWaves * 32 * C::kORedStride * sizeof(float) + 2 * kAttnWaves * 32 * sizeof(float);
   constexpr size_t kTiles = static_cast<size_t>(kAttnWaves) * C::kWaveLds;
   static_assert(kMerge <= kTiles, "merge buffers must fit in the tile memory");
-  static bool attr_done = false;
+  static std::atomic<uint64_t> attr_done{0};
   if (set_lds_once(&attn_stream_kernel<D>, kTiles, attr_done) != 0) return -6;
   if (plan.tau > 0) {
-    static bool list_attr_done = false;
+    static std::atomic<uint64_t> list_attr_done{0};
     if (set_lds_once(&attn_stream_list_kernel<D>, kTiles, list_attr_done) != 0) return -6;
-    static int n_cu = 0;
-    if (n_cu == 0) {
-      int dev = 0;
-      if (hipGetDevice(&dev) != hipSuccess ||
-          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
-        n_cu = 256;
-    }
+    const int n_cu = current_device_cus();
     hipLaunchKernelGGL((attn_stream_list_kernel<D>), dim3(2 * n_cu), dim3(kAttnThreads), kTiles, stream, P);
     return hipGetLastError() == hipSuccess ? 0 : -6;
   }
@@ -1064,16 +1047,15 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
 template <int D, int NW>
 static int launch_rows(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
   using RC = RowsCfg<D, NW>;
-  static bool attr_done = false;
+  static std::atomic<uint64_t> attr_done{0};
   if (set_lds_once(&attn_rows_kernel<D, NW>, RC::kLds, attr_done) != 0) return -6;
   dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
   hipLaunchKernelGGL((attn_rows_kernel<D, NW>), grid, dim3(RC::kThreads), RC::kLds, stream, P);
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-int launch_attn(const AttnArgs& a, hipStream_t stream) {
+int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
   if (a.B <= 0 || a.total_q <= 0) return 0;
-  const AttnPlan plan = make_plan(a);
   AttnParams P;
   P.q = static_cast<const uint16_t*>(a.q);
   P.k_pool = static_cast<const uint16_t*>(a.k_pool);

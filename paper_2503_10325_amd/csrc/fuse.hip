@@ -96,7 +96,7 @@ void launch_fuse(const FuseArgs& a, hipStream_t stream) {
   launch_row_stats(a.draft_logits, a.l_dtype, positions * a.N, nullptr, kBF16, 0, a.V, c, stats, stream);
   const int nseg = stats_segments(a.V);
   dim3 grid((a.V + kMixSeg - 1) / kMixSeg, positions);
-  if (a.V % 8 == 0)
+  if (a.V % 8 == 0 && aligned16(a.draft_logits) && aligned16(a.fused_probs))
     hipLaunchKernelGGL(fuse_mixture_kernel<true>, grid, dim3(kMixThreads), 0, stream, a.k_max, a.N, a.V,
                        a.k_len, a.conf, a.draft_logits, a.l_dtype, c, nseg, stats, a.fused_probs);
   else

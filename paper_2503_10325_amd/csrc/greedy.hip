@@ -144,7 +144,7 @@ void launch_accept_greedy(const GreedyArgs& a, hipStream_t stream) {
   const int nseg = argmax_segments(a.V);
   unsigned long long* keys = static_cast<unsigned long long*>(a.workspace);
   const dim3 grid(nseg, rows);
-  const bool vec = (a.V % 8 == 0);
+  const bool vec = (a.V % 8 == 0) && aligned16(a.target);
   if (vec)
     hipLaunchKernelGGL(row_argmax_kernel<true>, grid, dim3(kArgThreads), 0, stream, a.target, a.t_dtype, a.V, nseg, keys);
   else

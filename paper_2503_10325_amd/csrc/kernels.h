@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace specv {
@@ -17,7 +19,7 @@ void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void*
                       int n_nodes = 0);
 
 struct AcceptArgs {
-  int B, V, total_nodes, n_q_rows;
+  int B, V, total_nodes, n_q_rows, max_nodes;
   const int32_t* node_offsets;
   const int32_t* parent;
   const int32_t* draft_tokens;
@@ -33,9 +35,26 @@ struct AcceptArgs {
   float* dbg_ratio;
   void* workspace;
   bool target_stats_ready;     // the workspace already starts with the target rows' statistics
+  // per-call tuning (spec_accept_tuned); zero / negative = the library's choice
+  int path;                    // 0: library's choice, 1: statistics kernel + one-workgroup walk, 2: workgroup clusters
+  int levels, slices;          // cluster path: window levels, vocabulary slices per level
+  int patience;                // polls spent waiting for peer workgroups (< 0: default)
+  int helpers;                 // statistics + walk path: helper workgroups per request (< 0: default)
 };
+
+// ---- accept_cluster.hip -----------------------------------------------------------
+struct ClusterPlan {
+  int upt;                     // 16-byte loads per thread and row: a slice is upt x 8192 logits
+  int levels, slices;          // workgroups per request = levels x slices
+  int solo;                    // one workgroup per request computes every part itself
+};
+constexpr int kClusterMaxV = 32 * 4 * 8192;   // 32 slices of 4 x 8192 logits
+ClusterPlan make_cluster_plan(int B, int V, int max_nodes, bool tree, int n_cu, int want_levels, int want_slices);
+size_t cluster_msg_bytes(int B);
+void launch_accept_cluster(const AcceptArgs& a, const ClusterPlan& plan, int patience, void* msg, hipStream_t stream);
 size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V);
 void launch_accept(const AcceptArgs& a, hipStream_t stream);
+const char* accept_plan_name(const AcceptArgs& a, int n_cu);
 
 // ---- lmhead.hip ------------------------------------------------------------------
 struct LmHeadArgs {
@@ -133,7 +152,47 @@ struct AttnArgs {
   float* lse;
   void* workspace;
 };
-size_t attn_workspace_bytes(const AttnArgs& a);
-int launch_attn(const AttnArgs& a, hipStream_t stream);   // 0 or a negative spec_status
+// The launch plan is a pure function of the descriptor; the workspace-size query and the launch both
+// take the plan object the C-ABI layer computed, so the two can never disagree.
+struct AttnPlan {
+  int kind;           // 0: token-split kernel (<= 128 rows per KV head), 1: row-split, 4 waves, 2: row-split, 8 waves
+  int rows_per_wg;
+  int row_groups;
+  int chunk_tokens;
+  int max_chunks;
+  int tau;            // > 0: sorted-work-list launch of the token-split kernel, at most tau tiles per wave and item
+};
+AttnPlan make_attn_plan(const AttnArgs& a);
+size_t attn_workspace_bytes(const AttnArgs& a, const AttnPlan& plan);
+const char* attn_plan_name(const AttnPlan& plan);
+int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream);   // 0 or a negative spec_status
+
+// Vector (16-byte) accesses need 16-byte aligned base pointers; the launchers pick the scalar
+// variants of their kernels when a caller's pointer is not.
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// The dynamic-LDS limit of a kernel is raised once per device (the attribute belongs to the
+// device's copy of the function); the mask is the only state kept, and it is per device.
+template <typename K>
+inline int set_lds_once(K kernel, size_t lds, std::atomic<uint64_t>& done_mask) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -6;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev < 64 && (done_mask.load(std::memory_order_acquire) & bit)) return 0;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(lds)) != hipSuccess)
+    return -6;
+  if (dev < 64) done_mask.fetch_or(bit, std::memory_order_release);
+  return 0;
+}
+
+// Compute units of the current device, asked on every call (nothing is cached between calls).
+inline int current_device_cus() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  return n;
+}
 
 }  // namespace specv

@@ -609,10 +609,12 @@ int launch_lm_head(const LmHeadArgs& a, hipStream_t stream) {
   // row block of a panel in turn, measured 5-10 % faster than keeping the row blocks of one
   // vocabulary block adjacent when the last row block is partial, and equal otherwise.
   P.panel = (wide && P.nrb > 1) ? 128 : 0;
-  if (const char* e = getenv("SPECV_LM_PANEL")) {                       // development knob
+#ifdef SPECV_DEV_KNOBS
+  if (const char* e = getenv("SPECV_LM_PANEL")) {                       // sweeps only; normal builds read no environment
     const int v = atoi(e);
     if (v >= 0 && v <= 65536) P.panel = v;
   }
+#endif
   P.c = kLog2e / a.temperature;
   P.hidden = static_cast<const uint16_t*>(a.hidden);
   P.weight = static_cast<const uint16_t*>(a.weight);

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kRouteThreads) void routing_scores_kernel(
 
 void launch_routing_scores(const RoutingArgs& a, hipStream_t stream) {
   if (a.B <= 0 || a.N <= 0) return;
-  const bool vec = (a.E % 8 == 0);
+  const bool vec = (a.E % 8 == 0) && aligned16(a.embedding);
   if (vec)
     hipLaunchKernelGGL(routing_scores_kernel<true>, dim3(a.B, a.N), dim3(kRouteThreads), 0, stream, a.k_max, a.N, a.V, a.E,
                        a.k_len, a.conf, a.draft_tokens, a.accept_len, a.out_tokens, a.out_stride, a.embedding,

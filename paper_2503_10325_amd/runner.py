@@ -110,7 +110,13 @@ class DeviceAccept:
         ws = sv.spec_accept_workspace_size(self.B, self.total, self.draft_q.shape[0], self.V)
         self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=device)
 
-    def run(self, stream=None):
+    def run(self, stream=None, tuning=None):
+        if tuning is not None:
+            sv.spec_accept_tuned(tuning, self.B, self.total, self.max_nodes, self.node_offsets, self.parent,
+                                 self.draft_tokens, self.target, self.draft_q, self.q_kind, self.q_row,
+                                 self.temperature, self.u_accept, self.u_resample, self.accept_len, self.out_tokens,
+                                 self.stop_node, self.dbg_ratio, self.workspace, stream)
+            return
         sv.spec_accept(self.B, self.total, self.max_nodes, self.node_offsets, self.parent, self.draft_tokens,
                        self.target, self.draft_q, self.q_kind, self.q_row, self.temperature, self.u_accept,
                        self.u_resample, self.accept_len, self.out_tokens, self.stop_node, self.dbg_ratio,

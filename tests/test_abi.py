@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(sv.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
-    assert sv.lib().spec_abi_version() == 1
+    assert sv.lib().spec_abi_version() == 2
     assert sv.strerror(0) == "ok" and "workspace" in sv.strerror(-4)
 
 
@@ -136,3 +136,26 @@ def test_lm_head_validation_needs_no_gpu():
     a = L.spec_accept_prestats(2, 100, 4, 4, 2, null, null, null, null, 1, null, 0, 0, null, 1.0,
                                null, null, null, null, 3, null, null, null, 0, null)
     assert a == -3                              # statistics from the LM head describe bf16 logits
+
+
+def test_tuned_accept_and_plan_descriptions_need_no_gpu():
+    L = sv.lib()
+    null = ctypes.c_void_p(0)
+
+    def tuned(t, B=2, V=100, total=4, nq=4, maxn=2):
+        return L.spec_accept_tuned(None if t is None else ctypes.byref(t), B, V, total, nq, maxn, null, null, null,
+                                   null, 0, null, 0, 0, null, 1.0, null, null, null, null, 3, null, null, null, 0, null)
+
+    assert tuned(None) == -1                                    # like spec_accept: NULL tensors
+    assert tuned(sv.SpecAcceptTuning(path=3)) == -1             # tensors are checked first ...
+    assert tuned(sv.SpecAcceptTuning(path=2), B=0) == 0         # ... and an empty batch is nothing to do
+    desc = sv.make_attn_desc(batch=16, num_q_heads=32, num_kv_heads=8, head_dim=128, total_q=1024,
+                             max_q_per_req=64, max_pages_per_req=260, total_kv_tokens_hint=16 * 4160)
+    text = sv.spec_describe_attn_plan(desc)
+    assert "attn_" in text and "chunks" in text
+    text = sv.spec_describe_accept_plan(16, 128256, 64, True)
+    assert "accept_cluster_kernel" in text
+    text = sv.spec_describe_accept_plan(16, 128256, 64, True, target_dtype=sv.SPEC_F32)
+    assert "row_stats_kernel" in text
+    text = sv.spec_describe_accept_plan(16, 128256, 64, True, tuning=sv.SpecAcceptTuning(path=1))
+    assert "row_stats_kernel" in text

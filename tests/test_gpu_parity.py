@@ -143,7 +143,7 @@ ACCEPT_CASES = {
 }
 
 
-def _run_accept(rt, cfg, ai, fp32=False, q_kind=0, draft_q=None):
+def _run_accept(rt, cfg, ai, fp32=False, q_kind=0, draft_q=None, tuning=None):
     tl, dq = ai.target_logits, (ai.draft_q if draft_q is None else draft_q)
     if fp32:
         tl = W.bf16_bits_to_f32(tl)
@@ -153,15 +153,23 @@ def _run_accept(rt, cfg, ai, fp32=False, q_kind=0, draft_q=None):
                         ai.u_resample, temperature=cfg.temperature, qkind=q_kind)
     dev = rt.DeviceAccept(ai.st, tl, dq, ai.q_row, ai.draft_tokens, ai.u_accept, ai.u_resample,
                           temperature=cfg.temperature, q_kind=q_kind)
-    dev.run()
+    dev.run(tuning=tuning)
     return dev.results(), ref
 
 
+def _tuning(**kw):
+    from paper_2503_10325_amd import binding as sv
+    return sv.SpecAcceptTuning(**kw)
+
+
+@pytest.mark.parametrize("path", [0, 1, 2])
 @pytest.mark.parametrize("name", list(ACCEPT_CASES))
-def test_accept_matches_oracle(rt, name):
+def test_accept_matches_oracle(rt, name, path):
+    """path 0: the library's choice; 1: statistics pass over all rows + one walking workgroup per
+    request; 2: workgroup clusters that read only the walked rows (bf16 rows; other inputs fall back to 1)."""
     cfg, opt = ACCEPT_CASES[name]
     ai = W.make_accept_inputs(cfg, seed=4)
-    got, ref = _run_accept(rt, cfg, ai, fp32=opt.get("fp32", False))
+    got, ref = _run_accept(rt, cfg, ai, fp32=opt.get("fp32", False), tuning=_tuning(path=path) if path else None)
     bad, ties, B = compare_accept(got, ref, ai.st.n)
     print(f"{name}: near-ties {ties}/{B}, mean accept_len {ref['accept_len'].mean():.2f}")
     assert not bad, f"{name}: requests {bad} differ outside near-ties"
@@ -170,28 +178,107 @@ def test_accept_matches_oracle(rt, name):
     assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
 
 
-@pytest.mark.parametrize("helpers", ["0", "1", "2", "3"])
-def test_accept_helper_workgroups(rt, helpers, monkeypatch):
-    """Large vocabularies split every full pass over helper workgroups; any helper count (the library reads
-    the development knob at call time) must reproduce the oracle's decisions."""
-    monkeypatch.setenv("SPECV_WALK_HELPERS", helpers)
-    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=6, vocab=70001 if helpers == "2" else 128256)
+# (levels, slices) of the cluster path; 0 = the library's choice.  Vocabulary 128256 = 16 units of 8192 logits:
+# 4 slices of 4 units, 8 of 2, 16 of 1; 70000 = 9 units: 3 slices of 4 (the last with one), 5 of 2, 9 of 1.
+CLUSTER_SHAPES = [(0, 0), (1, 4), (2, 4), (4, 4), (1, 8), (3, 8), (1, 16), (2, 16)]
+
+
+@pytest.mark.parametrize("levels,slices", CLUSTER_SHAPES)
+def test_accept_cluster_shapes_tree(rt, levels, slices):
+    """Every split of a request over workgroups (window levels x vocabulary slices) reproduces the oracle's
+    decisions on tree drafts with a large vocabulary."""
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=6)
     ai = W.make_accept_inputs(cfg, seed=8)
-    got, ref = _run_accept(rt, cfg, ai)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=2, levels=levels, slices=slices))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+    assert (got["accept_len"] >= 0).all()
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+    assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"])) or ties
+
+
+@pytest.mark.parametrize("levels,slices,vocab,draft", [
+    (9, 2, 32000, ("linear", 8)), (4, 4, 32000, ("linear", 8)), (1, 1, 32000, ("linear_uniform", 1, 7)),
+    (5, 3, 70000, ("linear_uniform", 2, 10)), (2, 9, 70000, ("linear_uniform", 2, 10)), (3, 5, 70000, ("linear", 4)),
+    (16, 1, 8192, ("linear", 20)), (7, 1, 8200, ("linear", 3)),
+])
+def test_accept_cluster_shapes_linear(rt, levels, slices, vocab, draft):
+    """Linear drafts: windows longer and shorter than the draft, slices that end inside the vocabulary's
+    last unit, a slice beyond the vocabulary's end (8200 = one full unit + 8 logits)."""
+    cfg = W.scaled(C["c1_llama2_7b"], batch=7, vocab=vocab, draft=draft)
+    ai = W.make_accept_inputs(cfg, seed=21)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=2, levels=levels, slices=slices))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+
+
+@pytest.mark.parametrize("levels,slices", [(0, 0), (2, 8), (1, 4)])
+def test_accept_cluster_owner_walks_alone(rt, levels, slices):
+    """With no patience the first workgroup of every cluster never waits for its peers: it tells them to
+    leave and computes every slice's part itself, in the same order (what happens when peers are late because
+    other kernels fill the GPU).  Same decisions as the oracle AND bit-identical outputs to the cluster's."""
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=5)
+    ai = W.make_accept_inputs(cfg, seed=13)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=2, levels=levels, slices=slices, patience=0))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+    full, _ = _run_accept(rt, cfg, ai, tuning=_tuning(path=2, levels=levels, slices=slices))
+    for key in ("accept_len", "out_tokens", "stop_node"):
+        assert np.array_equal(got[key], full[key]), key
+    assert np.array_equal(got["ratio"], full["ratio"], equal_nan=True)
+
+
+def test_accept_cluster_one_workgroup_per_request(rt):
+    """More requests than compute units leave one workgroup per request (the library's choice is then the
+    statistics pass; the cluster path is forced here): it computes the slices' parts in turn."""
+    cfg = W.scaled(C["c4_llama70b_serving"], batch=300, vocab=40000)
+    ai = W.make_accept_inputs(cfg, seed=17)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=2))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+
+
+def test_accept_cluster_back_to_back_calls_share_a_workspace(rt):
+    """The message buffers of one call must not leak into the next (they are cleared by a kernel ahead of
+    the walk): two different batches through one workspace, twice."""
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=4, vocab=50000)
+    a1 = W.make_accept_inputs(cfg, seed=31)
+    a2 = W.make_accept_inputs(cfg, seed=32)
+    refs = [oracle.accept(a.st.node_offsets, a.st.parent, a.draft_tokens, a.target_logits, a.draft_q, a.q_row,
+                          a.u_accept, a.u_resample, temperature=cfg.temperature) for a in (a1, a2)]
+    devs = [rt.DeviceAccept(a.st, a.target_logits, a.draft_q, a.q_row, a.draft_tokens, a.u_accept, a.u_resample,
+                            temperature=cfg.temperature) for a in (a1, a2)]
+    devs[1].workspace = devs[0].workspace
+    for _ in range(2):
+        for d in devs:
+            d.run()
+    for a, d, ref in zip((a1, a2), devs, refs):
+        bad, ties, B = compare_accept(d.results(), ref, a.st.n)
+        assert not bad
+
+
+@pytest.mark.parametrize("helpers", [0, 1, 2, 3])
+def test_accept_helper_workgroups(rt, helpers):
+    """Statistics-pass path: large vocabularies split every full pass over helper workgroups; any helper
+    count must reproduce the oracle's decisions."""
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=6, vocab=70001 if helpers == 2 else 128256)
+    ai = W.make_accept_inputs(cfg, seed=8)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=1, helpers=helpers))
     bad, ties, B = compare_accept(got, ref, ai.st.n)
     assert not bad and ties <= max(1, B // 4)
     assert (got["accept_len"] >= 0).all()
     assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
 
 
-def test_accept_master_without_helper_answers(rt, monkeypatch):
-    """With no patience at all the master never waits for a helper and sums every segment itself (what it
-    does when helper workgroups are late because other kernels fill the GPU); late answers are ignored."""
-    monkeypatch.setenv("SPECV_WALK_HELPERS", "3")
-    monkeypatch.setenv("SPECV_WALK_PATIENCE", "0")
+def test_accept_master_without_helper_answers(rt):
+    """Statistics-pass path: with no patience at all the master never waits for a helper and sums every
+    segment itself (what it does when helper workgroups are late because other kernels fill the GPU); late
+    answers are ignored."""
     cfg = W.scaled(C["c2_tree_llama3_8b"], batch=5)
     ai = W.make_accept_inputs(cfg, seed=13)
-    got, ref = _run_accept(rt, cfg, ai)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=1, helpers=3, patience=0))
     bad, ties, B = compare_accept(got, ref, ai.st.n)
     assert not bad and ties <= max(1, B // 4)
     assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
