@@ -699,11 +699,19 @@ size_t accept_workspace_bytes(int B, int total_nodes, int n_q_rows, int V) {
   return accept_layout(B, total_nodes, n_q_rows, V).total;
 }
 
+// Where the cluster path wins (measured): every 8192-logit unit of a row gets a compute unit of its own and
+// the rows are long.  Short rows and batches with few compute units per request are faster through the
+// statistics pass over all rows, whose arithmetic spreads over the whole chip.
+static bool cluster_pays(int B, int V, int n_cu) {
+  const int units = (V + 8191) / 8192;
+  return units >= 8 && units <= 32 && static_cast<int64_t>(B) * units <= n_cu;
+}
+
 const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
   const bool vec = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
   const bool cluster_ok = vec && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
                           a.q_kind == 0 && !a.target_stats_ready;
-  const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && a.B <= n_cu));
+  const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && cluster_pays(a.B, a.V, n_cu)));
   if (!cluster) return "row_stats_kernel (all rows) + accept_walk_kernel (one workgroup per request, helper workgroups)";
   const ClusterPlan p = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
   return p.solo ? "accept_cluster_kernel (one workgroup per request, rows of the walked path only)"
@@ -723,7 +731,7 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
     const bool vec0 = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
     const bool cluster_ok = vec0 && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
                             a.q_kind == 0 && !a.target_stats_ready;
-    if (cluster_ok && (a.path == 2 || (a.path == 0 && a.B <= n_cu))) {
+    if (cluster_ok && (a.path == 2 || (a.path == 0 && cluster_pays(a.B, a.V, n_cu)))) {
       const ClusterPlan plan = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
       launch_accept_cluster(a, plan, a.patience >= 0 ? a.patience : 4000, ws + lay.msg_off, stream);
       return;

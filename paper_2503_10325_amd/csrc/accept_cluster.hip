@@ -35,11 +35,12 @@ namespace specv {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kClThreads = 1024;
+constexpr int kClThreads = 256;             // four waves, one per SIMD: the per-wave reductions and the replicated
+                                            // scalar steps cost a quarter of what sixteen waves would pay
 constexpr int kClWaves = kClThreads / kWave;
-constexpr int kClUnit = kClThreads * 8;        // logits one workgroup-wide 16-byte load covers
+constexpr int kClUnit = kClThreads * 8;        // logits one workgroup-wide 16-byte load covers (2048)
 constexpr int kClNodes = 64;
-constexpr int kClMaxUpt = 4;                   // units per slice: 4 x 32 KiB per row, two rows = 128 KiB of LDS
+constexpr int kClMaxUpt = 16;                  // units per slice: 16 x 4 KiB per row, two rows = 128 KiB of LDS
 constexpr int kClMaxParts = kClMaxUpt * kClWaves;
 constexpr unsigned kClAbort = 0xffffffffu;
 constexpr uint32_t kNegInf2 = 0xff80ff80u;     // two bf16 -inf
@@ -60,7 +61,7 @@ struct ClusterParams {
   int32_t* stop_node;
   float* dbg_ratio;
   int LV, SL;                     // window levels x vocabulary slices = workgroups per request
-  int UPT;                        // units (8192 logits) per slice
+  int UPT;                        // units (2048 logits) per slice
   int solo;                       // one workgroup per request, which computes all LV x SL parts itself
   int patience;                   // polls the owner spends on one round before it walks alone
   unsigned long long* msg;        // [B][2 buffers][C][2 messages][4 words]
@@ -76,6 +77,45 @@ template <typename T> __device__ __forceinline__ void cl_st(T* p, T v) {
 __device__ __forceinline__ void cl_unpack(u32x4 r, float (&x)[8]) {
   x[0] = bf16_lo(r[0]); x[1] = bf16_hi(r[0]); x[2] = bf16_lo(r[1]); x[3] = bf16_hi(r[1]);
   x[4] = bf16_lo(r[2]); x[5] = bf16_hi(r[2]); x[6] = bf16_lo(r[3]); x[7] = bf16_hi(r[3]);
+}
+
+// Whole-wave reductions through the data-parallel-primitive path of the vector ALU (a few cycles per
+// step, against a trip through the LDS crossbar per step for a shuffle): an inclusive scan inside
+// each row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of rows 0 and 2 is broadcast into rows 1 and 3
+// (row_bcast:15) and lane 31 into rows 2 and 3 (row_bcast:31); lane 63 then holds the result, which
+// is read back as a wave-uniform value.  Lanes without a source keep `old`, the identity.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave_sum_dpp(double x) {
+  x += dpp_f64<0x111, 0xf>(x);
+  x += dpp_f64<0x112, 0xf>(x);
+  x += dpp_f64<0x114, 0xf>(x);
+  x += dpp_f64<0x118, 0xf>(x);
+  x += dpp_f64<0x142, 0xa>(x);
+  x += dpp_f64<0x143, 0xc>(x);
+  const int lo = __builtin_amdgcn_readlane(__double2loint(x), 63);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
+  return __hiloint2double(hi, lo);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max_step(float x) {
+  const int ninf = 0xff800000;
+  const int y = __builtin_amdgcn_update_dpp(ninf, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return fmaxf(x, __int_as_float(y));
+}
+__device__ __forceinline__ float wave_max_dpp(float x) {
+  x = dpp_max_step<0x111, 0xf>(x);
+  x = dpp_max_step<0x112, 0xf>(x);
+  x = dpp_max_step<0x114, 0xf>(x);
+  x = dpp_max_step<0x118, 0xf>(x);
+  x = dpp_max_step<0x142, 0xa>(x);
+  x = dpp_max_step<0x143, 0xc>(x);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
 // Statistics of one level of the window: row maxima and reciprocal sums of 2^((l - max) c).
@@ -129,12 +169,12 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
   __shared__ double sh_e[64];
   __shared__ float sh_M[2][16];                // per level: maximum of the target row / the draft row
   __shared__ double sh_iZ[2][16];              //            reciprocal sums
-  __shared__ float sh_wm[2][kClWaves];
-  __shared__ double sh_part[kClMaxParts];      // per (unit, wave) sums of the slice held in LDS
+  __shared__ __align__(16) float sh_wm[2][kClWaves];
+  __shared__ double sh_ws[2][kClWaves];        // per-wave sums of the slice held in LDS
+  __shared__ double sh_part[kClMaxParts];      // its per-(unit, wave) sums (computed for the draw only)
   __shared__ double sh_invR[kClNodes];
   __shared__ float sh_invRf[kClNodes];
   __shared__ int sh_status;
-  __shared__ double sh_tot;
   const int n_parts = UPT * kClWaves;          // <= 64
 
   const int o = P.node_offsets[b];
@@ -142,6 +182,21 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
   n = n < 0 ? 0 : (n > kClNodes ? kClNodes : n);
   const int64_t trow0 = static_cast<int64_t>(o) + b;
   const double u_res = static_cast<double>(P.u_resample[b]);
+
+  // ---- the target row of this workgroup's level, when it is known before the node arrays arrive (the
+  // root's row; any level of a linear draft): its loads go out first and overlap the dependent reads below
+  const bool early_t = !P.solo && (my_lv == 0 || P.parent == nullptr) && my_lv - 1 < n;
+  u32x4 early_r[kClMaxUpt];
+  {
+    const uint16_t* tp = P.target + (trow0 + my_lv) * static_cast<int64_t>(V);
+    const u32x4 ninf = {kNegInf2, kNegInf2, kNegInf2, kNegInf2};
+#pragma unroll
+    for (int u = 0; u < kClMaxUpt; ++u) {
+      const int e = (my_sl * UPT + u) * kClUnit + tid * 8;
+      early_r[u] = ninf;
+      if (early_t && u < UPT && e < V) early_r[u] = *reinterpret_cast<const u32x4*>(tp + e);
+    }
+  }
 
   // ---- node arrays (indices come from device memory the host cannot check: clamp them) ----
   if (tid < kClNodes) {
@@ -159,14 +214,9 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
     sh_invRf[tid] = 0.f;
     sh_invR[tid] = 0.0;
   }
-  if (tid <= kClNodes) sh_fc[tid] = -2;
+  if (tid <= kClNodes) sh_fc[tid] = kClNodes;
   __syncthreads();
-  if (tid < n) {
-    const int par = sh_par[tid];
-    bool first = true;
-    for (int j = 0; j < tid; ++j) first = first && (sh_par[j] != par);
-    if (first) sh_fc[par + 1] = tid;
-  }
+  if (tid < n) atomicMin(&sh_fc[sh_par[tid] + 1], tid);      // first child = lowest index among the children
   // the two logits of every drafted token, kept in registers until the first round's loads are out
   float g_lp = 0.f, g_lq = 0.f;
   if (tid < n) {
@@ -175,13 +225,20 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
     g_lq = bf16_bits_to_float(P.draft_q[static_cast<int64_t>(sh_qrow[tid]) * V + x]);
   }
   __syncthreads();
+  if (tid <= kClNodes && sh_fc[tid] >= kClNodes) sh_fc[tid] = -2;   // no child
+  __syncthreads();
   const int my_parent = (lane < n) ? sh_par[lane] : -3;   // lanes >= n hold an impossible parent
 
   // ---- the slice held in LDS ----
   auto row_p = [&](int u) -> u32x4* { return reinterpret_cast<u32x4*>(cl_rows) + (u * kClThreads + tid); };
   auto row_q = [&](int u) -> u32x4* { return reinterpret_cast<u32x4*>(cl_rows) + ((UPT + u) * kClThreads + tid); };
-  // (a node < -1 stands for "the chain has ended")
-  auto load_slice = [&](int node, int sl) {
+  if (early_t) {
+#pragma unroll
+    for (int u = 0; u < kClMaxUpt; ++u)
+      if (u < UPT) *row_p(u) = early_r[u];
+  }
+  // (a node < -1 stands for "the chain has ended"; skip_t: the target part is in LDS already)
+  auto load_slice = [&](int node, int sl, bool skip_t = false) {
     const bool exists = node >= -1;
     node = max(node, -1);
     const int fcn = exists ? sh_fc[node + 1] : -2;
@@ -195,28 +252,20 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
       tp_r[u] = ninf;
       tq_r[u] = ninf;
       if (u < UPT && exists && e < V) {           // V is a multiple of 8: a chunk is inside or outside
-        tp_r[u] = *reinterpret_cast<const u32x4*>(tp + e);
+        if (!skip_t) tp_r[u] = *reinterpret_cast<const u32x4*>(tp + e);
         if (fcn >= 0) tq_r[u] = *reinterpret_cast<const u32x4*>(qp + e);
       }
     }
 #pragma unroll
     for (int u = 0; u < kClMaxUpt; ++u)
-      if (u < UPT) { *row_p(u) = tp_r[u]; *row_q(u) = tq_r[u]; }
-  };
-
-  // Total of the per-(unit, wave) parts the waves have just written, the same way for every caller.
-  auto parts_total = [&]() -> double {
-    __syncthreads();
-    if (wave == 0) {
-      double t = lane < n_parts ? sh_part[lane] : 0.0;
-      t = wave_sum(t);
-      if (lane == 0) sh_tot = t;
-    }
-    __syncthreads();
-    return sh_tot;
+      if (u < UPT) {
+        if (!skip_t) *row_p(u) = tp_r[u];
+        *row_q(u) = tq_r[u];
+      }
   };
 
   // Local statistics of the held slice: (max, sum 2^((l - max) c)) of the target part and the draft part.
+  // The results are valid in wave 0 (the wave that posts them).
   auto slice_stats = [&](bool have_q, float& mp, double& zp, float& mq, double& zq) {
     float tp = -INFINITY, tq = -INFINITY;
     for (int u = 0; u < UPT; ++u) {
@@ -228,53 +277,75 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
 #pragma unroll
       for (int j = 0; j < 8; ++j) tq = fmaxf(tq, x[j]);
     }
-    tp = wave_max(tp);
-    tq = wave_max(tq);
-    __syncthreads();                              // earlier readers of sh_wm and sh_part are done
-    if (lane == 0) { sh_wm[0][wave] = tp; sh_wm[1][wave] = tq; }
+    tp = wave_max_dpp(tp);
+    tq = wave_max_dpp(tq);
+    __syncthreads();                              // earlier readers of sh_wm and sh_ws are done
+    sh_wm[0][wave] = tp; sh_wm[1][wave] = tq;     // every lane of the wave stores the same value
     __syncthreads();
-    mp = sh_wm[0][0]; mq = sh_wm[1][0];
+    mp = -INFINITY; mq = -INFINITY;
 #pragma unroll
-    for (int w = 1; w < kClWaves; ++w) { mp = fmaxf(mp, sh_wm[0][w]); mq = fmaxf(mq, sh_wm[1][w]); }
+    for (int w = 0; w < kClWaves; w += 4) {
+      const float4 a = *reinterpret_cast<const float4*>(&sh_wm[0][w]);
+      const float4 b2 = *reinterpret_cast<const float4*>(&sh_wm[1][w]);
+      mp = fmaxf(fmaxf(mp, fmaxf(a.x, a.y)), fmaxf(a.z, a.w));
+      mq = fmaxf(fmaxf(mq, fmaxf(b2.x, b2.y)), fmaxf(b2.z, b2.w));
+    }
     const float sp = (mp == -INFINITY) ? 0.f : mp, sq = (mq == -INFINITY) ? 0.f : mq;
+    double ap = 0.0, aq = 0.0;
     for (int u = 0; u < UPT; ++u) {
       float x[8];
       cl_unpack(*row_p(u), x);
       float sum = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += fast_exp2((x[j] - sp) * c);
-      const double d = wave_sum(static_cast<double>(sum));
-      if (lane == 0) sh_part[u * kClWaves + wave] = d;
-    }
-    zp = parts_total();
-    zq = 0.0;
-    if (have_q) {
-      for (int u = 0; u < UPT; ++u) {
-        float x[8];
+      ap += static_cast<double>(sum);
+      if (have_q) {
         cl_unpack(*row_q(u), x);
-        float sum = 0.f;
+        sum = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) sum += fast_exp2((x[j] - sq) * c);
-        const double d = wave_sum(static_cast<double>(sum));
-        if (lane == 0) sh_part[u * kClWaves + wave] = d;
+        aq += static_cast<double>(sum);
       }
-      zq = parts_total();
     }
+    ap = wave_sum_dpp(ap);
+    aq = wave_sum_dpp(aq);
+    sh_ws[0][wave] = ap; sh_ws[1][wave] = aq;
+    __syncthreads();
+    zp = wave_sum_dpp(lane < kClWaves ? sh_ws[0][lane] : 0.0);
+    zq = wave_sum_dpp(lane < kClWaves ? sh_ws[1][lane] : 0.0);
   };
 
-  // Sum of the level-L weights of the held slice (the per (unit, wave) parts stay in sh_part).
+  // Sum of the level-L weights of the held slice (valid in every wave).
   auto slice_weight_sum = [&](const LevelStats& S, int L) -> double {
-    __syncthreads();                              // earlier readers of sh_part are done
+    double acc = 0.0;
     for (int u = 0; u < UPT; ++u) {
       float w[8];
       cl_weights(*row_p(u), *row_q(u), S, c, L, sh_invRf, w);
       float sum = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += w[j];
-      const double d = wave_sum(static_cast<double>(sum));
-      if (lane == 0) sh_part[u * kClWaves + wave] = d;
+      acc += static_cast<double>(sum);
     }
-    return parts_total();
+    acc = wave_sum_dpp(acc);
+    __syncthreads();                              // earlier readers of sh_ws are done
+    sh_ws[0][wave] = acc;
+    __syncthreads();
+    return wave_sum_dpp(lane < kClWaves ? sh_ws[0][lane] : 0.0);
+  };
+
+  // Per-(unit, wave) sums of the level-L weights of the held slice, in vocabulary order, for the draw.
+  auto slice_parts = [&](const LevelStats& S, int L) {
+    __syncthreads();
+    for (int u = 0; u < UPT; ++u) {
+      float w[8];
+      cl_weights(*row_p(u), *row_q(u), S, c, L, sh_invRf, w);
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += w[j];
+      const double d = wave_sum_dpp(static_cast<double>(sum));
+      sh_part[u * kClWaves + wave] = d;
+    }
+    __syncthreads();
   };
 
   // ---- messages ----
@@ -341,7 +412,7 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
         const int node = sh_chain[my_lv];
         float mp = -INFINITY, mq = -INFINITY;
         double zp = 0.0, zq = 0.0;
-        load_slice(node, my_sl);
+        load_slice(node, my_sl, guard == 0 && early_t);
         if (guard == 0 && tid < n) { sh_lp[tid] = g_lp; sh_lq[tid] = g_lq; }
         if (node >= -1) slice_stats(sh_fc[node + 1] >= 0, mp, zp, mq, zq);
         post(r, 0, zp, mp);
@@ -365,23 +436,21 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
         }
         __syncthreads();
       }
-      // ---- merge the slices' parts per level (wave 0: lane = message) ----
-      if (wave == 0) {
-        const int nm = 2 * C;
-        const int my = min(lane, nm - 1);
-        const int wg = my >> 1, kind = my & 1, lv = wg / SL;
-        float M = -INFINITY;
-        for (int s = 0; s < SL; ++s) M = fmaxf(M, sh_aux[2 * (lv * SL + s) + kind]);
-        const float mine = sh_aux[my];
-        const double e = (mine == -INFINITY) ? 0.0
-                         : sh_val[my] * exp2(static_cast<double>(mine - M) * static_cast<double>(c));
-        sh_e[my] = e;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        double Z = 0.0;
-        for (int s = 0; s < SL; ++s) Z += sh_e[2 * (lv * SL + s) + kind];
-        if (lane < nm && wg == lv * SL) { sh_M[kind][lv] = M; sh_iZ[kind][lv] = 1.0 / Z; }
+      // ---- merge the slices' parts per level: a wave per level, lane = (slice, row kind) ----
+      for (int lvw = wave; lvw < LV; lvw += kClWaves) {
+        const int sl = lane >> 1, kind = lane & 1;
+        const bool have = sl < SL;
+        const int idx = (lvw * SL + (have ? sl : 0)) * 2 + kind;
+        const float m = have ? sh_aux[idx] : -INFINITY;
+        const double z = have ? sh_val[idx] : 0.0;
+        const float M0 = wave_max_dpp(kind == 0 ? m : -INFINITY);
+        const float M1 = wave_max_dpp(kind == 1 ? m : -INFINITY);
+        const float M = kind ? M1 : M0;
+        const double e = (m == -INFINITY) ? 0.0 : z * exp2(static_cast<double>(m - M) * static_cast<double>(c));
+        const double Z0 = wave_sum_dpp(kind == 0 ? e : 0.0);
+        const double Z1 = wave_sum_dpp(kind == 1 ? e : 0.0);
+        sh_M[0][lvw] = M0; sh_M[1][lvw] = M1;                   // every lane stores the same values
+        sh_iZ[0][lvw] = 1.0 / Z0; sh_iZ[1][lvw] = 1.0 / Z1;
       }
       __syncthreads();
 
@@ -413,14 +482,8 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
             }
             __syncthreads();
           }
-          // total of the slices' sums (every wave of every workgroup: the same wave-level scan)
-          double inc = lane < SL ? sh_val[j * SL + lane] : 0.0;
-#pragma unroll
-          for (int d = 1; d < 32; d <<= 1) {
-            const double tq = __shfl_up(inc, d, kWave);
-            if (lane >= d) inc += tq;
-          }
-          return __shfl(inc, SL - 1, kWave);
+          // total of the slices' sums (every wave of every workgroup: the same wave-level reduction)
+          return wave_sum_dpp(lane < SL ? sh_val[j * SL + lane] : 0.0);
         };
 
         unsigned long long kids = __ballot(my_parent == cur && lane > cur);
@@ -486,11 +549,12 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
           s_hit = __ffsll(static_cast<long long>(hit)) - 1;       // no crossing (rounding): the last slice with positive mass
           before = __shfl(inc - mine, s_hit, kWave);
         }
-        if (solo) {                                // bring that slice and its per-(unit, wave) sums back
-          if (held_lv != j || held_sl != s_hit) { load_slice(sh_chain[j], s_hit); held_lv = j; held_sl = s_hit; }
-          (void)slice_weight_sum(S, level);
+        if (solo && (held_lv != j || held_sl != s_hit)) {       // bring that slice back
+          load_slice(sh_chain[j], s_hit);
+          held_lv = j; held_sl = s_hit;
         }
         if (solo || (my_lv == j && my_sl == s_hit)) {
+          slice_parts(S, level);
           // (unit, wave) part the crossing falls in: scan of the parts in vocabulary order (every wave alike)
           int p_hit;
           double run;
@@ -591,21 +655,25 @@ ClusterPlan make_cluster_plan(int B, int V, int max_nodes, bool tree, int n_cu, 
   int lv_need = max_nodes + 1;
   const int lv_cap = tree ? 4 : 9;
   if (lv_need > lv_cap) lv_need = lv_cap;
+  // The statistics of a slice are bound by the vector ALU of the one compute unit that holds it, so the
+  // slices are made as small as the workgroups available allow; what is left over buys window levels.
   int best_upt = 0, best_lv = 0, best_sl = 0;
-  for (int upt = 1; upt <= kClMaxUpt; upt *= 2) {
+  for (int upt = 1; upt <= kClMaxUpt && best_upt == 0; upt *= 2) {
     const int sl = (units + upt - 1) / upt;
+    if (upt < 4 && sl > 1 && want_slices <= 0) continue;      // rows are cut into slices of 8192 logits and more
     if (sl > cmax) continue;
     if (want_slices > 0 && sl != want_slices) continue;
     int lv = cmax / sl;
     if (lv > lv_need) lv = lv_need;
     if (want_levels > 0) { if (want_levels * sl > cmax || want_levels > 16) continue; lv = want_levels; }
-    if (lv > best_lv) { best_lv = lv; best_upt = upt; best_sl = sl; }
+    best_lv = lv; best_upt = upt; best_sl = sl;
   }
   if (best_upt != 0 && best_lv * best_sl == 1) p.solo = 1;       // a cluster of one exchanges nothing
   if (best_upt == 0) {
     // not even one slice set fits (or the batch exceeds the compute units): one workgroup per request,
-    // which computes the parts of ceil(units / 4) slices in turn
-    best_upt = units >= 4 ? 4 : (units >= 2 ? 2 : 1);
+    // which computes the parts of ceil(units / 16) slices in turn
+    best_upt = kClMaxUpt;
+    while (best_upt > 1 && units <= best_upt / 2) best_upt /= 2;
     if (want_slices > 0) {
       for (int upt = 1; upt <= kClMaxUpt; upt *= 2) if ((units + upt - 1) / upt == want_slices) best_upt = upt;
     }

@@ -205,7 +205,7 @@ int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, i
   const char* name = accept_plan_name(a, n_cu);
   const ClusterPlan p = make_cluster_plan(B, V, max_nodes_per_req, is_tree != 0, n_cu, a.levels, a.slices);
   snprintf(buf, buf_bytes, "%s; cluster plan for this shape: %d level(s) x %d slice(s) of %d logits%s", name,
-           p.solo ? 1 : p.levels, p.slices, p.upt * 8192, p.solo ? " (one workgroup)" : "");
+           p.solo ? 1 : p.levels, p.slices, p.upt * 2048, p.solo ? " (one workgroup)" : "");
   return SPEC_OK;
 }
 

@@ -44,11 +44,11 @@ struct AcceptArgs {
 
 // ---- accept_cluster.hip -----------------------------------------------------------
 struct ClusterPlan {
-  int upt;                     // 16-byte loads per thread and row: a slice is upt x 8192 logits
+  int upt;                     // 16-byte loads per thread and row: a slice is upt x 2048 logits
   int levels, slices;          // workgroups per request = levels x slices
   int solo;                    // one workgroup per request computes every part itself
 };
-constexpr int kClusterMaxV = 32 * 4 * 8192;   // 32 slices of 4 x 8192 logits
+constexpr int kClusterMaxV = 32 * 16 * 2048;  // 32 slices of 16 x 2048 logits
 ClusterPlan make_cluster_plan(int B, int V, int max_nodes, bool tree, int n_cu, int want_levels, int want_slices);
 size_t cluster_msg_bytes(int B);
 void launch_accept_cluster(const AcceptArgs& a, const ClusterPlan& plan, int patience, void* msg, hipStream_t stream);
