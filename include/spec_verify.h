@@ -210,6 +210,24 @@ int32_t spec_accept_tuned(
     const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
     int32_t* stop_node, float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream);
 
+/* spec_accept for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same results.
+ * The workspace is a fixed array inside the library (spec_accept_noalloc_max_workspace() bytes, 4 MiB,
+ * one per GPU, held until the process ends); the call allocates and frees nothing.  Problems whose
+ * spec_accept_workspace_size exceeds that are rejected with SPEC_ERR_WORKSPACE and nothing is
+ * enqueued; SPEC_ERR_LAUNCH if the array's address cannot be obtained.  Every call on one GPU uses
+ * that GPU's one array: calls that may overlap on one GPU (different streams, different threads)
+ * race and must be serialised by the caller.  What has to start at zero is cleared by a kernel of
+ * the call itself. */
+size_t spec_accept_noalloc_max_workspace(void);
+int32_t spec_accept_noalloc(
+    int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
+    const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+    const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
+    int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
+    const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
+    int32_t* stop_node, float* dbg_ratio, void* stream);
+
 /* One-line description of what spec_accept launches for this shape on the current device
  * (host; for logs and benchmark reports). */
 int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V,

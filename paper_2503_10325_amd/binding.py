@@ -23,6 +23,7 @@ EXPORTS = [
     "spec_fuse_drafts_workspace_size", "spec_fuse_drafts",
     "spec_accept_workspace_size", "spec_accept", "spec_accept_tuned",
     "spec_describe_attn_plan", "spec_describe_accept_plan",
+    "spec_accept_noalloc", "spec_accept_noalloc_max_workspace",
     "spec_accept_greedy_workspace_size", "spec_accept_greedy",
     "spec_routing_scores", "spec_adaptive_speculation", "spec_compact_kv",
     "spec_row_stats_size", "spec_lm_head_workspace_size", "spec_lm_head", "spec_accept_prestats",
@@ -95,6 +96,10 @@ def lib() -> ctypes.CDLL:
         L.spec_accept_prestats.argtypes = L.spec_accept.argtypes
         L.spec_accept_tuned.restype = i32
         L.spec_accept_tuned.argtypes = [ctypes.POINTER(SpecAcceptTuning)] + L.spec_accept.argtypes
+        L.spec_accept_noalloc.restype = i32
+        L.spec_accept_noalloc.argtypes = L.spec_accept.argtypes[:-3] + [vp]
+        L.spec_accept_noalloc_max_workspace.restype = sz
+        L.spec_accept_noalloc_max_workspace.argtypes = []
         L.spec_describe_attn_plan.restype = i32
         L.spec_describe_attn_plan.argtypes = [ctypes.POINTER(SpecAttnDesc), ctypes.c_char_p, sz]
         L.spec_describe_accept_plan.restype = i32
@@ -217,6 +222,22 @@ def spec_accept_tuned(tuning, B, total_nodes, max_nodes_per_req, node_offsets, p
                                  _ptr(workspace), ws_bytes, _stream(stream))
     if rc != SPEC_OK:
         raise SpecError("spec_accept_tuned", rc)
+
+
+def spec_accept_noalloc(B, total_nodes, max_nodes_per_req, node_offsets, parent, draft_tokens, target_logits,
+                        draft_q, q_kind, q_row, temperature, u_accept, u_resample, accept_len, out_tokens,
+                        stop_node=None, dbg_ratio=None, stream=None) -> None:
+    """spec_accept on the library's built-in scratch array: no workspace argument, no allocation."""
+    V = target_logits.shape[1]
+    n_q_rows = 0 if draft_q is None else draft_q.shape[0]
+    rc = lib().spec_accept_noalloc(B, V, total_nodes, n_q_rows, max_nodes_per_req, _ptr(node_offsets), _ptr(parent),
+                                   _ptr(draft_tokens), _ptr(target_logits), _dtype_code(target_logits), _ptr(draft_q),
+                                   SPEC_BF16 if draft_q is None else _dtype_code(draft_q), int(q_kind), _ptr(q_row),
+                                   float(temperature), _ptr(u_accept), _ptr(u_resample), _ptr(accept_len),
+                                   _ptr(out_tokens), out_tokens.shape[1], _ptr(stop_node), _ptr(dbg_ratio),
+                                   _stream(stream))
+    if rc != SPEC_OK:
+        raise SpecError("spec_accept_noalloc", rc)
 
 
 def spec_describe_attn_plan(desc: SpecAttnDesc) -> str:

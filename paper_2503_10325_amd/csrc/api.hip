@@ -7,6 +7,23 @@
 
 using namespace specv;
 
+// Scratch memory of spec_accept_noalloc: one array per GPU, held until the process ends.  In host code
+// the array's name is only a stand-in; its device address is asked for once per device and kept.
+constexpr size_t kNoallocScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static void* noalloc_scratch_ptr() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  g_scratch_ptr[dev].store(p, std::memory_order_release);      // racing threads store the same address
+  return p;
+}
+
 extern "C" {
 
 const char* spec_strerror(int32_t status) {
@@ -15,7 +32,7 @@ const char* spec_strerror(int32_t status) {
     case SPEC_ERR_NULL: return "a required pointer is NULL";
     case SPEC_ERR_SHAPE: return "invalid or inconsistent size";
     case SPEC_ERR_UNSUPPORTED: return "unsupported head_dim, page_size, dtype or mode";
-    case SPEC_ERR_WORKSPACE: return "workspace missing or too small";
+    case SPEC_ERR_WORKSPACE: return "workspace missing or too small (or the problem exceeds the built-in scratch)";
     case SPEC_ERR_LAUNCH: return "HIP launch failed";
     default: return "unknown status";
   }
@@ -188,6 +205,24 @@ int32_t spec_accept_tuned(const spec_accept_tuning* tuning, int32_t B, int32_t V
                       draft_tokens, target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature,
                       u_accept, u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, workspace,
                       workspace_bytes, stream);
+}
+
+size_t spec_accept_noalloc_max_workspace(void) { return kNoallocScratchBytes; }
+
+int32_t spec_accept_noalloc(int32_t B, int32_t V, int32_t total_nodes, int32_t n_q_rows, int32_t max_nodes_per_req,
+                            const int32_t* node_offsets, const int32_t* parent, const int32_t* draft_tokens,
+                            const void* target_logits, int32_t target_dtype, const void* draft_q, int32_t q_dtype,
+                            int32_t q_kind, const int32_t* q_row, float temperature, const float* u_accept,
+                            const float* u_resample, int32_t* accept_len, int32_t* out_tokens, int32_t out_stride,
+                            int32_t* stop_node, float* dbg_ratio, void* stream) {
+  if (B < 0 || V <= 0 || total_nodes < 0 || n_q_rows < 0) return SPEC_ERR_SHAPE;
+  if (accept_workspace_bytes(B, total_nodes, n_q_rows, V) > kNoallocScratchBytes) return SPEC_ERR_WORKSPACE;
+  void* ws = noalloc_scratch_ptr();
+  if (!ws) return SPEC_ERR_LAUNCH;
+  return accept_entry(false, nullptr, B, V, total_nodes, n_q_rows, max_nodes_per_req, node_offsets, parent,
+                      draft_tokens, target_logits, target_dtype, draft_q, q_dtype, q_kind, q_row, temperature,
+                      u_accept, u_resample, accept_len, out_tokens, out_stride, stop_node, dbg_ratio, ws,
+                      kNoallocScratchBytes, stream);
 }
 
 int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t max_nodes_per_req,
