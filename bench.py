@@ -2,11 +2,14 @@
 """Benchmark of the parallel-verification hot path on one MI355X.
 
 One step = one pass of the whole path over one synthetic batch: spec_verify_attn,
-spec_fuse_drafts and spec_accept enqueued on one stream.  Inputs are resident in
-HBM before the timed region; several independent copies of every input are rotated
-so that no step finds its data in the last-level cache.  Prints ONE JSON line.
+spec_fuse_drafts (workloads with several drafters) and spec_accept enqueued on one
+stream.  Inputs are resident in HBM before the timed region; several independent
+copies of every input are rotated so that no step finds its data in the last-level
+cache.  Prints ONE JSON line: the headline workload (the largest single-GPU
+configuration, c4_llama70b_serving) at the top level, and one entry per measured
+workload in `workloads`.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--also a,b,c|none]
 """
 import argparse
 import json
@@ -22,6 +25,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 METRIC = "verified draft tokens/sec + achieved HBM GB/s (verify-attn+accept), 1 MI355X"
+HEADLINE = "c4_llama70b_serving"
+OTHERS = "c1_llama2_7b,c2_tree_llama3_8b,c3_fusion"
 
 
 def parse_args():
@@ -29,7 +34,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c1_llama2_7b")
+    ap.add_argument("--workload", default=HEADLINE, help="the workload of the top-level fields")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated further workloads measured in the same run and reported in `workloads` "
+                         f"(default: {OTHERS} when --workload is the headline workload, else none)")
     ap.add_argument("--copies", type=int, default=4, help="independent input copies rotated per step")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -37,7 +45,10 @@ def parse_args():
                     help="also run a plain device copy of this many MiB (known traffic for counter scaling)")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching every call from the host")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0,
+                    help="budget of the oracle timing leg, split evenly over the measured workloads")
+    ap.add_argument("--min-event-steps", type=int, default=100,
+                    help="steps of the separate event-timed loop the per-step median/p10/p90 come from")
     ap.add_argument("--fuse", choices=["auto", "always"], default="auto",
                     help="auto: spec_fuse_drafts runs on workloads with several drafters (its only use in the method); "
                          "always: single-drafter workloads also run it with N = 1 (an identity)")
@@ -47,6 +58,8 @@ def parse_args():
     ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
                     help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
                          "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
+    ap.add_argument("--accept-path", type=int, default=0, choices=[0, 1, 2],
+                    help="0: the library's choice; 1: statistics pass over all rows + walk; 2: workgroup clusters")
     ap.add_argument("--fuse-mode", choices=["argmax", "mixture"], default="argmax",
                     help="multi-drafter workloads: argmax = the paper's confidence rule (Eq. 4, the headline path); "
                          "mixture = confidence-weighted average of the drafters' distributions (Section 2.2), written "
@@ -55,13 +68,13 @@ def parse_args():
                     help="also run the projection that produces the target logits (spec_lm_head on synthetic "
                          "[rows, d_model] hidden states and a [vocab, d_model] bf16 weight, d_model = heads x "
                          "head_dim) inside the step; acceptance then starts from its statistics "
-                         "(spec_accept_prestats).  Not the headline step: the line gains an lm_head object")
+                         "(spec_accept_prestats).  Not the headline step: the entry gains an lm_head object")
     return ap.parse_args()
 
 
-def read_traffic(workload):
-    """HBM bytes per attention launch derived from rocprofv3 --pmc runs, if recorded."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+def read_traffic(key):
+    """HBM bytes per launch derived from rocprofv3 --pmc runs, if recorded under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{key}.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -71,13 +84,14 @@ def read_traffic(workload):
 
 
 class Step:
-    """Device state of one input copy and the three calls of one step."""
+    """Device state of one input copy and the calls of one step."""
 
-    def __init__(self, cfg, a, ai, runner, sv, accept_mode="sampling", fuse="auto", routing=False, lm=None,
-                 fuse_mode="argmax"):
+    def __init__(self, cfg, a, ai, runner, sv, args, lm=None, want_debug=False):
         import torch
+        accept_mode, fuse, routing, fuse_mode = args.accept_mode, args.fuse, args.routing, args.fuse_mode
         self.routing = None
         self.head = None
+        self.tuning = sv.SpecAcceptTuning(path=args.accept_path) if args.accept_path else None
         self.attn = runner.DeviceAttn(a, want_lse=False)
         st = a.st
         if ai.fusion is not None:
@@ -92,7 +106,7 @@ class Step:
                                               self.fuse.q_row.view(-1), self.fuse.fused_token.view(-1),
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
                                               q_kind=sv.SPEC_Q_PROBS if mixture else sv.SPEC_Q_LOGITS,
-                                              want_debug=False)
+                                              want_debug=want_debug)
         else:
             # single drafter: token fusion has nothing to fuse.  With --fuse always it still runs with
             # N = 1 (an identity) and, for linear drafts of uniform length, feeds the acceptance step.
@@ -118,27 +132,35 @@ class Step:
                                               self.fuse.q_row.view(-1) if uniform else ai.q_row,
                                               self.fuse.fused_token.view(-1) if uniform else ai.draft_tokens,
                                               ai.u_accept, ai.u_resample, temperature=cfg.temperature,
-                                              want_debug=False)
+                                              want_debug=want_debug)
         if routing and ai.fusion is not None and accept_mode == "sampling":
             from paper_2503_10325_amd import workloads as W
             f = ai.fusion
             emb = runner.bf16_to_device(W._normal_bf16(W._rng(0, cfg.name, "embedding"), (cfg.vocab, 4096)), "cuda")
             t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
             scores = torch.zeros((cfg.batch, f.n_drafters), dtype=torch.float32, device="cuda")
-            args = (t(f.k_len), t(f.conf), t(f.draft_tokens), self.accept.accept_len, self.accept.out_tokens, emb, scores)
-            self.routing = lambda: sv.spec_routing_scores(*args)
+            rargs = (t(f.k_len), t(f.conf), t(f.draft_tokens), self.accept.accept_len, self.accept.out_tokens, emb, scores)
+            self.routing = lambda: sv.spec_routing_scores(*rargs)
+        self.sampling = accept_mode == "sampling"
         if accept_mode == "greedy":
             # same target rows and draft tokens, no draft distributions or uniforms
             self.accept = runner.DeviceGreedy(st, self.accept.target, self.accept.draft_tokens)
+        self.prestats = False
         if lm is not None:
             # the target rows come from the projection (written into the tensor the acceptance step
             # reads), their statistics go to the head of the acceptance workspace
-            sampling = accept_mode == "sampling"
             self.head = runner.DeviceLmHead(lm, temperature=cfg.temperature,
-                                            stats=self.accept.workspace if sampling else None)
+                                            stats=self.accept.workspace if self.sampling else None)
             self.head.logits = self.accept.target
-            if sampling:
-                self.accept.run = self.accept.run_prestats
+            self.prestats = self.sampling
+
+    def run_accept(self):
+        if self.prestats:
+            self.accept.run_prestats()
+        elif self.sampling:
+            self.accept.run(tuning=self.tuning)
+        else:
+            self.accept.run()
 
     def run(self):
         self.attn.run()
@@ -146,17 +168,19 @@ class Step:
             self.head.run()
         if self.fuse is not None:
             self.fuse.run()
-        self.accept.run()
+        self.run_accept()
         if self.routing is not None:
             self.routing()
 
 
 def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None, fuse_mode="argmax"):
-    """The oracle, as it stands, timed on the host cores over whole batches of the workload."""
+    """The oracle, as it stands, timed on the host cores over whole batches of the workload.
+    Also returns the oracle's count of near-ties (decisions within 1e-6 of the uniform)."""
     import oracle
     reps, t_total = 0, 0.0
     tokens = int(a.st.total)
     lm_note, lm_s = "", 0.0
+    near = {"n": None}
     if lm is not None:
         # the projection is timed once on a few rows and scaled to all of them (it is linear in rows)
         rows = lm.hidden.shape[0]
@@ -165,6 +189,7 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None, fuse_mod
         oracle.lm_head(lm.hidden[:r], lm.weight, temperature=cfg.temperature)
         lm_s = (time.perf_counter() - t0) * rows / r
         lm_note = f"; plus the projection, timed on {r} of {rows} rows and scaled: {lm_s:.2f} s per pass"
+
     def one_pass():
         oracle.verify_attn(a.q, a.k_pool, a.v_pool, a.block_table, a.st.ctx_len, a.st.node_offsets,
                            a.st.parent, want_lse=False)
@@ -182,8 +207,9 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None, fuse_mod
         if accept_mode == "greedy":
             oracle.accept_greedy(a.st.node_offsets, a.st.parent, toks, ai.target_logits)
         else:
-            oracle.accept(a.st.node_offsets, a.st.parent, toks, ai.target_logits, dq, qrow, ai.u_accept,
-                          ai.u_resample, temperature=cfg.temperature, qkind=qkind)
+            r = oracle.accept(a.st.node_offsets, a.st.parent, toks, ai.target_logits, dq, qrow, ai.u_accept,
+                              ai.u_resample, temperature=cfg.temperature, qkind=qkind)
+            near["n"] = int(np.count_nonzero(r["near_tie"]))
 
     while reps < 1 or (t_total < budget_s and reps < 1000):
         t0 = time.perf_counter()
@@ -195,29 +221,61 @@ def cpu_baseline(cfg, a, ai, budget_s, accept_mode="sampling", lm=None, fuse_mod
                sample=f"{reps} pass(es) over the full {cfg.name} batch ({tokens} draft tokens each), "
                       f"{t_total:.2f} s of oracle time" + lm_note)
     # one more pass on a single thread where that stays within a few seconds (not the LM-head product)
-    if lm is None and threads > 1 and t_total / reps * threads < 8.0:
+    if lm is None and threads > 1 and t_total / reps * threads < 4.0:
         oracle.set_threads(1)
         t0 = time.perf_counter()
         one_pass()
         out["single_thread_value"] = tokens / (time.perf_counter() - t0)
         oracle.set_threads(threads)
-    return out
+    return out, near["n"]
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
+def accept_min_rows(st, ratio, accept_len, stop_node):
+    """Logit rows the walked paths need (the algorithmic minimum of the acceptance step): for every node
+    the walk stood on, its target row and - if it tested a child - the draft row of its children, read
+    once; one further read of that row pair for every rejection (the residual's mass).  Derived from the
+    library's own outputs: `ratio` is not NaN exactly on the nodes whose token was tested."""
+    rows = 0
+    for b in range(len(st.n)):
+        o, n = int(st.node_offsets[b]), int(st.n[b])
+        par = np.arange(-1, n - 1) if st.parent is None else st.parent[o:o + n]
+        tested = ~np.isnan(ratio[o:o + n])
+        path = set()
+        c = int(stop_node[b])
+        while c >= 0:
+            path.add(c)
+            c = int(par[c])
+        stood = [-1] + sorted(path)
+        rows += len(stood)                                        # target rows
+        rows += sum(1 for c in stood if np.any(tested & (par == c)))     # draft rows
+        rejected = int(tested.sum()) - len(path)
+        rows += 2 * rejected
+    return rows
+
+
+def event_times_us(torch, fn, n, copies):
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    torch.cuda.synchronize()
+    for i in range(n):
+        ev[i][0].record()
+        fn(copies[i % len(copies)])
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    return np.array([e0.elapsed_time(e1) for e0, e1 in ev]) * 1e3
+
+
+def pct(x):
+    return {"median": float(np.median(x)), "p10": float(np.percentile(x, 10)), "p90": float(np.percentile(x, 90)),
+            "mean": float(np.mean(x))}
+
+
+def measure(name, args, cpu_seconds):
+    """Builds the inputs of one workload, times K steps, and returns its report entry."""
     import torch
     from paper_2503_10325_amd import binding as sv
     from paper_2503_10325_amd import runner
     from paper_2503_10325_amd import workloads as W
-    sv.lib()
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    cfg = W.CONFIGS[args.workload]
+    cfg = W.CONFIGS[name]
     a = W.make_attn_inputs(cfg, seed=args.seed)
     lm = None
     if args.lm_head:
@@ -233,8 +291,7 @@ def main():
         ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st, target_logits=host_logits)
     else:
         ai = W.make_accept_inputs(cfg, seed=args.seed, st=a.st)
-    copies = [Step(cfg, a, ai, runner, sv, args.accept_mode, args.fuse, args.routing, lm, args.fuse_mode)
-              for _ in range(max(1, args.copies))]
+    copies = [Step(cfg, a, ai, runner, sv, args, lm) for _ in range(max(1, args.copies))]
     torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -259,6 +316,8 @@ def main():
             g.replay()
         torch.cuda.synchronize()
 
+    # ---- the timed region: exactly K steps ----
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     if graphs is None:
         for i in range(args.steps):
@@ -269,28 +328,18 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    # Duration of the dominant kernel: the attention entry point alone, one launch per input copy
-    # in rotation, each bracketed by HIP events on the launch stream.
-    n_ev = max(20, min(args.steps, 200))
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
-    torch.cuda.synchronize()
-    for i in range(n_ev):
-        c = copies[i % len(copies)]
-        ev[i][0].record()
-        c.attn.run()
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    attn_ms = np.array([e0.elapsed_time(e1) for e0, e1 in ev])
-    attn_s = float(attn_ms.mean()) * 1e-3
+    # ---- separate event-timed loops: per-step distribution, and each call of the step on its own ----
+    n_ev = max(args.min_event_steps, min(args.steps, 400))
+    step_us = event_times_us(torch, lambda c: c.run(), n_ev, copies)
+    attn_us = event_times_us(torch, lambda c: c.attn.run(), n_ev, copies)
+    accept_us = event_times_us(torch, lambda c: c.run_accept(), n_ev, copies)
+    attn_s = float(attn_us.mean()) * 1e-6
+    accept_s = float(accept_us.mean()) * 1e-6
+
     lm_obj = None
     if lm is not None:
-        for i in range(n_ev):
-            c = copies[i % len(copies)]
-            ev[i][0].record()
-            c.head.run()
-            ev[i][1].record()
-        torch.cuda.synchronize()
-        lm_s = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e-3
+        lm_us = event_times_us(torch, lambda c: c.head.run(), n_ev, copies)
+        lm_s = float(lm_us.mean()) * 1e-6
         rows = lm.hidden.shape[0]
         w_bytes = cfg.vocab * cfg.d_model * 2
         lm_bytes = w_bytes + rows * cfg.d_model * 2 + rows * cfg.vocab * 2       # weight + hidden read, logits written
@@ -307,6 +356,80 @@ def main():
                                "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak,
                                "traffic": read_traffic("lm_head_c1") if cfg.name == "c1_llama2_7b" else None,
                                "algorithmic_bytes": lm_bytes, "flops": lm_flops}}
+
+    # ---- what the step produced (the library's own outputs of copy 0) ----
+    tokens = int(a.st.total)
+    c0 = copies[0]
+    if args.accept_mode == "sampling":          # one untimed step that also writes the tested ratios
+        c0.accept.dbg_ratio = torch.zeros(max(tokens, 1), dtype=torch.float32, device="cuda")
+    c0.run()
+    res = c0.accept.results()
+    accepted_per_step = int(res["accept_len"].sum()) + cfg.batch          # accepted drafts + one emitted token each
+    attn_bytes, attn_flops = W.attention_bytes_flops(cfg, a.st)
+    n_draft_rows_read = int(a.st.total) if ai.fusion else ai.draft_q.shape[0]
+    all_rows = ai.target_logits.shape[0] + (0 if args.accept_mode == "greedy" else n_draft_rows_read)
+    all_rows_bytes = all_rows * cfg.vocab * 2
+    if args.accept_mode == "sampling" and res.get("ratio") is not None:
+        min_rows = accept_min_rows(a.st, res["ratio"], res["accept_len"], res["stop_node"])
+    else:
+        min_rows = all_rows                                                # greedy verification reads every target row
+    min_bytes = min_rows * cfg.vocab * (4 if (ai.fusion is not None and args.fuse_mode == "mixture") else 2)
+    if ai.fusion is not None and args.fuse_mode == "mixture" and args.accept_mode == "sampling":
+        # the drafters' rows are streamed twice by the fusion call (statistics, weighted sum), the fused fp32
+        # rows are written once and read once by the acceptance statistics
+        n_fused = ai.fusion.conf.shape[0] * ai.fusion.conf.shape[1]
+        all_rows_bytes = (ai.target_logits.shape[0] * 2 + ai.fusion.draft_logits.shape[0] * 2 * 2 + n_fused * 4 * 2) * cfg.vocab
+
+    attn_plan = sv.spec_describe_attn_plan(c0.attn.desc)
+    if args.accept_mode == "greedy":
+        accept_plan = "row_argmax_kernel + greedy_walk_kernel"
+    elif lm is not None:
+        accept_plan = "row_stats_kernel (draft rows only) + accept_walk_kernel, target statistics from spec_lm_head"
+    else:
+        accept_plan = sv.spec_describe_accept_plan(cfg.batch, cfg.vocab, int(a.st.n.max()), a.st.parent is not None,
+                                                   q_kind=c0.accept.q_kind, q_dtype=sv._dtype_code(c0.accept.draft_q),
+                                                   tuning=c0.tuning)
+    step_s = elapsed / args.steps
+    attn_ach = attn_bytes / attn_s / 1e9
+    acc_ach = min_bytes / accept_s / 1e9
+    entry = {
+        "workload": cfg.name,
+        "batch": cfg.batch, "draft_tokens_per_step": tokens,
+        "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
+        "context": str(cfg.ctx), "draft": str(cfg.draft), "vocab": cfg.vocab,
+        "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": step_s * 1e3,
+        "tokens_per_s": tokens / step_s,
+        "accepted_tokens_per_step": accepted_per_step,
+        "accepted_tokens_per_s": accepted_per_step / step_s,
+        "step_us": pct(step_us), "step_us_samples": int(n_ev),
+        "calls_per_step": ["spec_verify_attn"] + (["spec_lm_head"] if lm is not None else []) +
+                          (["spec_fuse_drafts"] if c0.fuse is not None else []) +
+                          [("spec_accept_prestats" if lm is not None else "spec_accept")
+                           if args.accept_mode == "sampling" else "spec_accept_greedy"] +
+                          (["spec_routing_scores"] if c0.routing is not None else []),
+        # algorithmic bytes of the step (attention: K/V once per KV head + Q + O; acceptance: the rows the walked
+        # paths need) over the step's wall time
+        "step_hbm_gbs": (attn_bytes + min_bytes) / step_s / 1e9,
+        "step_hbm_frac": (attn_bytes + min_bytes) / step_s / 1e9 / HBM_PEAK_GBS,
+        # the same with every target row and every referenced draft row counted once (what an all-rows pass moves)
+        "step_hbm_gbs_all_rows": (attn_bytes + all_rows_bytes) / step_s / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn: " + attn_plan + "; duration is the whole call, incl. "
+                                               "the chunk-combine kernel where the context is split",
+                     "achieved": attn_ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": attn_ach / HBM_PEAK_GBS,
+                     "traffic": read_traffic(cfg.name), "algorithmic_bytes": attn_bytes,
+                     "launch_us": pct(attn_us), "mfma_tflops": attn_flops / attn_s / 1e12},
+        "accept_roofline": {"bound": "hbm", "kernel": ("spec_accept: " if args.accept_mode == "sampling" else
+                                                       "spec_accept_greedy: ") + accept_plan + "; duration is the whole call",
+                            "achieved": acc_ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": acc_ach / HBM_PEAK_GBS,
+                            "traffic": read_traffic("accept_" + cfg.name),
+                            "algorithmic_bytes": min_bytes, "algorithmic_rows": int(min_rows),
+                            "all_rows_bytes": all_rows_bytes, "all_rows": int(all_rows),
+                            "launch_us": pct(accept_us)},
+        "near_ties": None,
+    }
+    if lm_obj is not None:
+        entry["lm_head"] = lm_obj
     if args.calibration_copy_mb > 0:
         # a plain copy kernel of known size: reads N MiB and writes N MiB
         src = torch.empty(args.calibration_copy_mb << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -314,68 +437,66 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
+    del copies, c0, graphs
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        entry["cpu_baseline"], entry["near_ties"] = cpu_baseline(cfg, a, ai, cpu_seconds, args.accept_mode, lm,
+                                                                 args.fuse_mode)
+    return entry
 
-    tokens = int(a.st.total)
-    attn_bytes, attn_flops = W.attention_bytes_flops(cfg, a.st)
-    # draft rows the statistics pass reads: with several drafters only the rows a fused token was drawn from
-    n_logit_rows = ai.target_logits.shape[0] + (int(a.st.total) if ai.fusion else ai.draft_q.shape[0])
-    if args.accept_mode == "greedy":
-        n_logit_rows = ai.target_logits.shape[0]          # no draft distributions are read
-    accept_bytes = n_logit_rows * cfg.vocab * 2
-    if ai.fusion is not None and args.fuse_mode == "mixture" and args.accept_mode == "sampling":
-        # the drafters' rows are streamed twice by the fusion call (statistics, weighted sum), the fused fp32
-        # rows are written once and read once by the acceptance statistics
-        n_fused = ai.fusion.conf.shape[0] * ai.fusion.conf.shape[1]
-        accept_bytes = (ai.target_logits.shape[0] * 2 + ai.fusion.draft_logits.shape[0] * 2 * 2 + n_fused * 4 * 2) * cfg.vocab
-    # the attention kernel the library's plan picks for this shape (all query rows that share a KV head)
-    max_rows = int(a.st.n.max()) * (cfg.n_q_heads // cfg.n_kv_heads)
-    total_tok = int((a.st.ctx_len.astype(np.int64) + a.st.n).sum())
-    ragged = cfg.batch <= 128 and total_tok * 100 < 85 * cfg.batch * a.max_pages * 16     # the library's own rule
-    if max_rows > 128:
-        attn_kernel = f"attn_rows_kernel<{cfg.head_dim},8> (row-split, 8 waves share each K/V tile)"
-    elif ragged:
-        attn_kernel = (f"attn_stream_list_kernel<{cfg.head_dim}> (token-split body, device-built work list sorted by "
-                       f"length, 2 persistent workgroups per CU)")
-    else:
-        attn_kernel = f"attn_stream_kernel<{cfg.head_dim}> (token-split, one workgroup per request x KV head x context chunk)"
-    achieved = attn_bytes / attn_s / 1e9
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2503_10325_amd import binding as sv
+    sv.lib()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    also = args.also
+    if also is None:
+        also = OTHERS if args.workload == HEADLINE else "none"
+    names = [args.workload] + [n for n in also.split(",") if n and n != "none" and n != args.workload]
+    share = args.cpu_seconds / len(names)
+    entries = [measure(n, args, share) for n in names]
+    head = entries[0]
     out = {
         "metric": METRIC,
-        "value": tokens * args.steps / elapsed,
+        "value": head["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "launch_mode": "eager" if graphs is None else "hip_graph_replay",
+        "launch_mode": "hip_graph_replay" if args.graph else "eager",
         "accept_mode": args.accept_mode,
-        "fuse_mode": args.fuse_mode if ai.fusion is not None else None,
-        "calls_per_step": ["spec_verify_attn"] + (["spec_lm_head"] if lm is not None else []) +
-                          (["spec_fuse_drafts"] if copies[0].fuse is not None else []) +
-                          [("spec_accept_prestats" if lm is not None else "spec_accept")
-                           if args.accept_mode == "sampling" else "spec_accept_greedy"] +
-                          (["spec_routing_scores"] if copies[0].routing is not None else []),
-        "config": {"workload": cfg.name, "batch": cfg.batch, "draft_tokens_per_step": tokens,
-                   "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
-                   "context": str(cfg.ctx), "draft": str(cfg.draft), "vocab": cfg.vocab,
-                   "input_copies_rotated": len(copies)},
-        "step_hbm_gbs": (attn_bytes + accept_bytes) / (elapsed / args.steps) / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn: " + attn_kernel + "; duration is the whole call, incl. the chunk-combine kernel where the context is split",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic(cfg.name), "algorithmic_bytes": attn_bytes,
-                     "launch_us_mean": attn_s * 1e6, "launch_us_p10": float(np.percentile(attn_ms, 10)) * 1e3,
-                     "launch_us_p90": float(np.percentile(attn_ms, 90)) * 1e3,
-                     "mfma_tflops": attn_flops / attn_s / 1e12},
+        "fuse_mode": args.fuse_mode,
+        "config": {"workload": head["workload"], "batch": head["batch"],
+                   "draft_tokens_per_step": head["draft_tokens_per_step"], "q_heads": head["q_heads"],
+                   "kv_heads": head["kv_heads"], "head_dim": head["head_dim"], "context": head["context"],
+                   "draft": head["draft"], "vocab": head["vocab"], "input_copies_rotated": max(1, args.copies)},
+        "accepted_tokens_per_s": head["accepted_tokens_per_s"],
+        "near_ties": head["near_ties"],
+        "step_us": head["step_us"],
+        "step_hbm_gbs": head["step_hbm_gbs"],
+        "step_hbm_frac": head["step_hbm_frac"],
+        "roofline": head["roofline"],
+        "accept_roofline": head["accept_roofline"],
     }
-    if lm_obj is not None:
-        out["lm_head"] = lm_obj
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, a, ai, args.cpu_seconds, args.accept_mode, lm, args.fuse_mode)
+    if "lm_head" in head:
+        out["lm_head"] = head["lm_head"]
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    out["workloads"] = entries
     print(json.dumps(out))
 
 
