@@ -104,6 +104,17 @@ __device__ __forceinline__ u32x4 zero4() {
 }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values as two fp16 in one word (round toward zero: never rounds a finite value to infinity).
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+// A word of two bf16 values as two fp16 values.  Exact for magnitudes in [2^-14, 65504] (bf16 carries 8
+// significant bits, fp16 11); smaller magnitudes land on the fp16 subnormal grid (absolute error < 2^-24),
+// larger ones saturate at 65504.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) { return pack_f16(bf16_lo(w), bf16_hi(w)); }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   bf16x2 x = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
@@ -697,6 +708,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
 #pragma unroll
     for (int i = 0; i < RC::kTpt; ++i)
       if (i >= left) vr[i] = zero4();
+    // V goes to LDS as fp16 (the weights P are fp16 too: 11 significant bits in ONE matrix term)
+#pragma unroll
+    for (int i = 0; i < RC::kTpt; ++i)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) vr[i][k] = bf16x2_to_f16x2(vr[i][k]);
     const u32x4 w0 = vr[0], w1 = vr[1];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -753,9 +769,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     // V^T operand of the first 16 tokens is fetched while the scores are reduced
     const unsigned char* v_rd = v_lds + ((ln & 7) * 18 + (ln >> 3)) * RC::kVStride + 16 * lh;
     auto v_frag = [&](int chunk, int db) {      // chunk = 16-token group 0..3 of the tile
-      return as_bf16x8(*reinterpret_cast<const u32x4*>(v_rd + 4 * db * RC::kVStride + 32 * chunk));
+      return __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(v_rd + 4 * db * RC::kVStride + 32 * chunk));
     };
-    bf16x8 va[C::kDBlocks];
+    f16x8 va[C::kDBlocks];
 #pragma unroll
     for (int db = 0; db < C::kDBlocks; ++db) va[db] = v_frag(0, db);
 
@@ -786,43 +802,39 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
-    // P^T in two bf16 terms (value + rounding residual), 16 tokens at a time
+    // P^T as fp16 (weights lie in [0, 1]: 11 significant bits, against 8 of bf16, keep the output's
+    // error at the level of its own bf16 rounding with a single matrix term), 16 tokens at a time
     float psum = 0.f;
-    auto p_chunk = [&](int chunk, bf16x8& phi, bf16x8& plo) {
+    auto p_chunk = [&](int chunk, f16x8& ph) {
       const int tb = chunk >> 1, s = chunk & 1;
-      u32x4 hi, lo;
+      u32x4 hw;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float p0 = fast_exp2(fmaf(sacc[tb][8 * s + 2 * j], P.c, -m_safe));
         const float p1 = fast_exp2(fmaf(sacc[tb][8 * s + 2 * j + 1], P.c, -m_safe));
         psum += p0 + p1;
-        const uint32_t h = pack_bf16(p0, p1);
-        hi[j] = h;
-        lo[j] = pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
+        hw[j] = pack_f16(p0, p1);
       }
-      phi = __builtin_bit_cast(bf16x8, hi);
-      plo = __builtin_bit_cast(bf16x8, lo);
+      ph = __builtin_bit_cast(f16x8, hw);
     };
-    bf16x8 phi, plo;
-    p_chunk(0, phi, plo);
+    f16x8 ph;
+    p_chunk(0, ph);
 #pragma unroll
     for (int chunk = 0; chunk < 4; ++chunk) {
       __builtin_amdgcn_sched_barrier(0);
-      bf16x8 vn[C::kDBlocks];
+      f16x8 vn[C::kDBlocks];
       if (chunk + 1 < 4) {
 #pragma unroll
         for (int db = 0; db < C::kDBlocks; ++db) vn[db] = v_frag(chunk + 1, db);
       }
 #pragma unroll
-      for (int db = 0; db < C::kDBlocks; ++db) {
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], phi, oacc[db], 0, 0, 0);
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], plo, oacc[db], 0, 0, 0);
-      }
+      for (int db = 0; db < C::kDBlocks; ++db)
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[db], ph, oacc[db], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (chunk + 1 < 4) {
-        bf16x8 nhi, nlo;
-        p_chunk(chunk + 1, nhi, nlo);          // VALU work in the shadow of the MFMAs just issued
-        phi = nhi; plo = nlo;
+        f16x8 nh;
+        p_chunk(chunk + 1, nh);                // VALU work in the shadow of the MFMAs just issued
+        ph = nh;
 #pragma unroll
         for (int db = 0; db < C::kDBlocks; ++db) va[db] = vn[db];
       }
@@ -859,8 +871,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   if (!active) return;
   l_run = half_sum(l_run);
   if (!valid) return;
+  // The weights were truncated to fp16 (round toward zero): every one is low by a factor that is uniform in
+  // [0, 2^-11], 2^-12 on average, while the denominator l was summed from the unrounded weights.  The
+  // average is put back here; what remains is the zero-mean part (2^-12 at most per weight).
+  constexpr float kRtzFix = 1.f + 1.f / 4096.f;
   if (nchunks == 1) {
-    const float inv = 1.f / l_run;
+    const float inv = kRtzFix / l_run;
 #pragma unroll
     for (int db = 0; db < C::kDBlocks; ++db)
 #pragma unroll
@@ -886,7 +902,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
       for (int r4 = 0; r4 < 4; ++r4) {
         const int d = 32 * db + 8 * r4 + 4 * lh;
         *reinterpret_cast<float4*>(o + d) =
-            make_float4(oacc[db][4 * r4], oacc[db][4 * r4 + 1], oacc[db][4 * r4 + 2], oacc[db][4 * r4 + 3]);
+            make_float4(oacc[db][4 * r4] * kRtzFix, oacc[db][4 * r4 + 1] * kRtzFix, oacc[db][4 * r4 + 2] * kRtzFix,
+                        oacc[db][4 * r4 + 3] * kRtzFix);
       }
     if (lh == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(m_run, l_run);
   }
