@@ -5,18 +5,21 @@
 // Work decomposition.  All n*G query rows that share a KV head are processed together so every
 // K/V byte is fetched once per KV head; long requests are cut into context chunks whose
 // unnormalised partial results attn_combine_kernel merges (split-KV).  Two bodies:
-//   token-split (stream_item, <= 128 rows per KV head): a 4-wave workgroup per (request, KV head,
-//     chunk); every wave streams its own 32-token tiles (2 cache pages): coalesced 16-byte global
-//     loads -> registers -> the wave's private LDS tile -> MFMA operands; waves that share a
-//     32-row query block merge through LDS.  Launched grid-mapped (attn_stream_kernel) or, for
-//     small ragged batches, from a work list built on the device and sorted by length
-//     (attn_stream_list_kernel).
-//   row-split (attn_rows_kernel, more rows): the waves of a workgroup stage 64-token
-//     tiles together (double-buffered LDS) and each owns one block of 32 query rows.
-// In both, S^T = K Q^T and O^T = V^T P^T run on v_mfma_f32_32x32x16_bf16 with the tokens as the
-// M dimension, so each lane owns one query column and the online-softmax statistics need a
-// single exchange between the half-waves.  V is transposed on its way into LDS (token pairs
-// packed with v_perm).
+//   token-split (stream_item, up to 64 rows per KV head, up to 128 in ragged batches): a 4-wave
+//     workgroup per (request, KV head, chunk); every wave streams its own 32-token tiles (2 cache
+//     pages): coalesced 16-byte global loads -> registers -> the wave's private LDS tile -> MFMA
+//     operands; waves that share a 32-row query block merge through LDS.  Launched grid-mapped
+//     (attn_stream_kernel) or, for small ragged batches, from a work list built on the device and
+//     sorted by length (attn_stream_list_kernel).
+//   row-split (attn_rows_kernel, more rows): the 4 or 8 waves of a workgroup stage 64-token
+//     tiles together (double-buffered LDS, two tiles of global loads in flight) and each owns
+//     one block of 32 query rows.
+// In both, S^T = K Q^T runs on v_mfma_f32_32x32x16_bf16 with the tokens as the M dimension, so
+// each lane owns one query column and the online-softmax statistics need a single exchange
+// between the half-waves.  V is transposed on its way into LDS (token pairs packed with v_perm).
+// O^T = V^T P^T: the token-split body keeps bf16 operands (weights as a high and a low bf16 term);
+// the row-split body converts V to fp16 while staging it and uses fp16 weights in one
+// v_mfma_f32_32x32x16_f16 term.
 #include <stdlib.h>
 
 #include "common.h"
@@ -531,7 +534,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnP
   }
   __syncthreads();
   const int total = sh_first[P.B];
-  for (int item = blockIdx.x; item < total; item += gridDim.x) {
+  // Round r hands out items r*G .. r*G+G-1 (G workgroups), in workgroup order on even rounds and in reverse
+  // on odd ones: the workgroup that got the longest item of one round gets the shortest of the next.
+  for (int round = 0;; ++round) {
+    const int slot = (round & 1) ? static_cast<int>(gridDim.x - 1 - blockIdx.x) : static_cast<int>(blockIdx.x);
+    const int item = round * static_cast<int>(gridDim.x) + slot;
+    if (item >= total) break;
     int lo = 0, hi = P.B;                         // largest s with sh_first[s] <= item
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
@@ -564,7 +572,8 @@ struct RowsCfg {
   static constexpr int kVBytes = kVRows * kVStride;
   static constexpr int kStage = kKBytes + kVBytes;
   static constexpr int kMaxChunkPages = 1024;              // a chunk spans at most 16384 tokens
-  static constexpr int kLds = 2 * kStage + 768 + kMaxChunkPages * 4;
+  static constexpr int kPagePad = 32;                      // page-table entries kept past a chunk's last page
+  static constexpr int kLds = 2 * kStage + 768 + (kMaxChunkPages + kPagePad) * 4;
   static_assert(kTpt == 4 || kTpt == 2, "unsupported tile/thread combination");
 };
 
@@ -624,7 +633,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     __syncthreads();
   }
 
-  // ---- this wave's block of 32 query rows ----
+  // ---- this wave's 32 query rows ----
   const int wrow0 = row0 + 32 * wave;
   const bool active = wrow0 < R;                // wave-uniform
   const int row = wrow0 + ln;
@@ -664,7 +673,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   // Page ids of the whole chunk go to LDS once, so that the tile loads depend on no global read.
   const int lp0 = t_begin / kPage;
   const int np = (t_end + kPage - 1) / kPage - lp0;          // >= 1 pages touched by this chunk
-  for (int i = tid; i < np; i += RC::kThreads) sh_pages[i] = bt[lp0 + i];
+  // (entries past the chunk's last page repeat it: tile numbers past the end need no clamp)
+  for (int i = tid; i < np + RC::kPagePad; i += RC::kThreads) sh_pages[i] = bt[lp0 + min(i, np - 1)];
   __syncthreads();
 
   // Loads are unconditional (addresses clamped to the chunk's last page): positions past the
@@ -676,18 +686,31 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   const int k_lane_off = (k_tok_in_load % kPage) * D + (tid % RC::kCh) * 8;
   const int k_page_in_load = k_tok_in_load / kPage;                   // wave-uniform
   const int v_lane_off = (vtok0 % kPage) * D + vc * 8;
-  auto issue_loads = [&](int t, u32x4 (&kr)[RC::kLoads], u32x4 (&vr)[RC::kLoads]) {
+  // The page ids of tile t are read from LDS right after the loads of tile t-1 were issued, a whole tile step
+  // before they are needed: the address of a load then waits on no LDS round trip.
+  int pg[RC::kLoads + 1];
+  auto fetch_pages = [&](int t) {
+    const int* tp = sh_pages + min(RC::kT * t / kPage, np + RC::kPagePad - RC::kT / kPage);
+#pragma unroll
+    for (int j = 0; j < RC::kLoads; ++j) pg[j] = tp[(j * kTokPerLoadWg) / kPage + k_page_in_load];
+    pg[RC::kLoads] = tp[vtok0 / kPage];
+  };
+  auto issue_loads = [&](u32x4 (&kr)[RC::kLoads], u32x4 (&vr)[RC::kLoads]) {
 #pragma unroll
     for (int j = 0; j < RC::kLoads; ++j) {
-      const int pidx = (RC::kT * t + j * kTokPerLoadWg) / kPage + k_page_in_load;
-      const int page = __builtin_amdgcn_readfirstlane(sh_pages[min(pidx, np - 1)]);
+      const int page = __builtin_amdgcn_readfirstlane(pg[j]);
       const uint16_t* base = P.k_pool + page * page_elems + head_off;
       kr[j] = *reinterpret_cast<const u32x4*>(base + k_lane_off);
     }
-    const int page = __builtin_amdgcn_readfirstlane(sh_pages[min((RC::kT * t + vtok0) / kPage, np - 1)]);
+    const int page = __builtin_amdgcn_readfirstlane(pg[RC::kLoads]);
     const uint16_t* vp = P.v_pool + page * page_elems + head_off + v_lane_off;
 #pragma unroll
     for (int i = 0; i < RC::kTpt; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vp + i * D);
+  };
+  // issue the loads of tile t (tiles are issued in order: t is the one whose page ids were fetched last)
+  auto issue_tile = [&](int t, u32x4 (&kr)[RC::kLoads], u32x4 (&vr)[RC::kLoads]) __attribute__((always_inline)) {
+    issue_loads(kr, vr);
+    fetch_pages(t + 1);
   };
 
   auto store_tile = [&](int stage, int t, u32x4 (&kr)[RC::kLoads], u32x4 (&vr)[RC::kLoads]) {
@@ -704,10 +727,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     const int pos = 8 * (a4 & 1) + 4 * (a4 >> 1) + sub;
     const int col = (16 * s16 + pos) * 2;
     // never multiply stale cache slots (past ctx+n) into O: stage them as zeros
-    const int left = L - (t_begin + RC::kT * t + vtok0);      // tokens of this thread that exist
+    if (t_begin + RC::kT * (t + 1) > L) {                     // only the last tile (and the ones past it)
+      const int left = L - (t_begin + RC::kT * t + vtok0);    // tokens of this thread that exist
 #pragma unroll
-    for (int i = 0; i < RC::kTpt; ++i)
-      if (i >= left) vr[i] = zero4();
+      for (int i = 0; i < RC::kTpt; ++i)
+        if (i >= left) vr[i] = zero4();
+    }
     // V goes to LDS as fp16 (the weights P are fp16 too: 11 significant bits in ONE matrix term)
 #pragma unroll
     for (int i = 0; i < RC::kTpt; ++i)
@@ -734,18 +759,38 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     }
   };
 
-  // One 64-token tile = one online-softmax step.  Program order is pinned (sched_barrier) so that
-  // LDS operand reads run two steps ahead of the MFMAs that consume them and the exponentials of
-  // the next 16 tokens are computed while the PV MFMAs of the current 16 tokens execute.
-  auto compute_tile = [&](int stage, int t) {
+  // One 64-token tile = one online-softmax step in two parts (scores, output) that share these registers.
+  f32x16 sacc[2];
+  f16x8 ph, va[C::kDBlocks];
+  float m_safe = 0.f, m_next = -INFINITY, alpha = 1.f, psum = 0.f;
+  auto v_frag = [&](int stage, int chunk, int db) {      // chunk = 16-token group 0..3 of the tile
+    const unsigned char* v_rd = smem + stage * RC::kStage + RC::kKBytes + ((ln & 7) * 18 + (ln >> 3)) * RC::kVStride + 16 * lh;
+    return __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(v_rd + 4 * db * RC::kVStride + 32 * chunk));
+  };
+  // P^T as fp16 (weights lie in [0, 2^8]: 11 significant bits, against 8 of bf16, keep the output's error at the
+  // level of its own bf16 rounding with a single matrix term), 16 tokens at a time
+  auto p_chunk = [&](int chunk, f16x8& dst) __attribute__((always_inline)) {
+    const int tb = chunk >> 1, sg = chunk & 1;
+    u32x4 hw;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float p0 = fast_exp2(fmaf(sacc[tb][8 * sg + 2 * j], P.c, -m_safe));
+      const float p1 = fast_exp2(fmaf(sacc[tb][8 * sg + 2 * j + 1], P.c, -m_safe));
+      psum += p0 + p1;
+      hw[j] = pack_f16(p0, p1);
+    }
+    dst = __builtin_bit_cast(f16x8, hw);
+  };
+
+  // First half: S = K Q^T (operand reads from LDS run two steps ahead of the matrix instructions that consume
+  // them), mask, row maxima, rescale, the weights of the first 16 tokens.
+  auto tile_scores = [&](int stage, int t) __attribute__((always_inline)) {
     const unsigned char* k_lds = smem + stage * RC::kStage;
-    const unsigned char* v_lds = k_lds + RC::kKBytes;
     const int tok0 = t_begin + RC::kT * t;
     const unsigned char* k_rd = k_lds + ln * RC::kKStride + 16 * lh;
     auto k_frag = [&](int ks, int tb) {
       return as_bf16x8(*reinterpret_cast<const u32x4*>(k_rd + 32 * tb * RC::kKStride + 32 * ks));
     };
-    f32x16 sacc[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -767,13 +812,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
     }
     __builtin_amdgcn_sched_barrier(0);
     // V^T operand of the first 16 tokens is fetched while the scores are reduced
-    const unsigned char* v_rd = v_lds + ((ln & 7) * 18 + (ln >> 3)) * RC::kVStride + 16 * lh;
-    auto v_frag = [&](int chunk, int db) {      // chunk = 16-token group 0..3 of the tile
-      return __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(v_rd + 4 * db * RC::kVStride + 32 * chunk));
-    };
-    f16x8 va[C::kDBlocks];
 #pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db) va[db] = v_frag(0, db);
+    for (int db = 0; db < C::kDBlocks; ++db) va[db] = v_frag(stage, 0, db);
 
     if (tok0 + RC::kT > ctx) {                   // tile reaches the drafts or the end: apply the mask
 #pragma unroll
@@ -793,77 +833,78 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
       for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[tb][r]);
     tmax *= P.c;                                   // c > 0: the maximum commutes with the scaling
     tmax = half_max(tmax);
-    const float m_new = fmaxf(m_run, tmax);
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_safe);
+    // The running maximum only has to bound the exponents: it follows the true maximum when that is first
+    // finite or has grown by more than 8 (weights then reach 2^8 at most, exact in fp16 and fp32); the
+    // accumulator is rescaled on those steps alone, and the final O / l is the same quotient either way.
+    m_next = fmaxf(m_run, tmax);
+    if (m_run != -INFINITY && tmax <= m_run + 8.f) m_next = m_run;
+    m_safe = (m_next == -INFINITY) ? 0.f : m_next;
+    alpha = fast_exp2(m_run - m_safe);
     if (__any(alpha != 1.f)) {
 #pragma unroll
       for (int db = 0; db < C::kDBlocks; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
-    // P^T as fp16 (weights lie in [0, 1]: 11 significant bits, against 8 of bf16, keep the output's
-    // error at the level of its own bf16 rounding with a single matrix term), 16 tokens at a time
-    float psum = 0.f;
-    auto p_chunk = [&](int chunk, f16x8& ph) {
-      const int tb = chunk >> 1, s = chunk & 1;
-      u32x4 hw;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float p0 = fast_exp2(fmaf(sacc[tb][8 * s + 2 * j], P.c, -m_safe));
-        const float p1 = fast_exp2(fmaf(sacc[tb][8 * s + 2 * j + 1], P.c, -m_safe));
-        psum += p0 + p1;
-        hw[j] = pack_f16(p0, p1);
-      }
-      ph = __builtin_bit_cast(f16x8, hw);
-    };
-    f16x8 ph;
+    psum = 0.f;
     p_chunk(0, ph);
+  };
+
+  // Second half: O += P V, 16 tokens at a time, with the exponentials of the next 16 tokens between the
+  // matrix instructions of the current ones.
+  auto tile_output = [&](int stage) __attribute__((always_inline)) {
 #pragma unroll
     for (int chunk = 0; chunk < 4; ++chunk) {
       __builtin_amdgcn_sched_barrier(0);
       f16x8 vn[C::kDBlocks];
+      f16x8 nh;
       if (chunk + 1 < 4) {
 #pragma unroll
-        for (int db = 0; db < C::kDBlocks; ++db) vn[db] = v_frag(chunk + 1, db);
+        for (int db = 0; db < C::kDBlocks; ++db) vn[db] = v_frag(stage, chunk + 1, db);
       }
 #pragma unroll
       for (int db = 0; db < C::kDBlocks; ++db)
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[db], ph, oacc[db], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
       if (chunk + 1 < 4) {
-        f16x8 nh;
-        p_chunk(chunk + 1, nh);                // VALU work in the shadow of the MFMAs just issued
+        p_chunk(chunk + 1, nh);
+        // A wave issues in order: matrix instructions queued back to back would hold the weights of the next
+        // 16 tokens behind them.  One matrix instruction, one operand read, then a quarter of the vector work.
+#pragma unroll
+        for (int i = 0; i < C::kDBlocks; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+        }
         ph = nh;
 #pragma unroll
         for (int db = 0; db < C::kDBlocks; ++db) va[db] = vn[db];
       }
     }
     l_run = l_run * alpha + psum;
-    m_run = m_new;
+    m_run = m_next;
   };
 
   // ---- pipeline: tile t is computed from LDS while tile t+1 sits in registers ----
-  issue_loads(0, krA, vrA);
-  if (ntiles > 1) issue_loads(1, krB, vrB);
+  // Loads and LDS stores are issued unconditionally, also for tile numbers past the end (their addresses are
+  // clamped to the chunk's last page, their V rows staged as zeros, and they are never computed): with the
+  // same number of loads outstanding on every path, the wait before a store covers only the older register
+  // set and leaves the newer one in flight.  A branch around an issue would make that wait a full drain.
+  fetch_pages(0);
+  issue_tile(0, krA, vrA);
+  issue_tile(1, krB, vrB);
   store_tile(0, 0, krA, vrA);
-  if (ntiles > 2) issue_loads(2, krA, vrA);
+  issue_tile(2, krA, vrA);
   __syncthreads();
   for (int t = 0; t < ntiles; t += 2) {
     // LDS stage 0 holds tile t, set B tile t+1, set A tile t+2
-    if (active) compute_tile(0, t);
-    if (t + 1 < ntiles) {
-      store_tile(1, t + 1, krB, vrB);
-      if (t + 3 < ntiles) issue_loads(t + 3, krB, vrB);
-    }
+    if (active) { tile_scores(0, t); tile_output(0); }
+    store_tile(1, t + 1, krB, vrB);
+    issue_tile(t + 3, krB, vrB);
     __syncthreads();
-    if (t + 1 >= ntiles) break;
     // LDS stage 1 holds tile t+1, set A tile t+2, set B tile t+3
-    if (active) compute_tile(1, t + 1);
-    if (t + 2 < ntiles) {
-      store_tile(0, t + 2, krA, vrA);
-      if (t + 4 < ntiles) issue_loads(t + 4, krA, vrA);
-    }
+    if (active && t + 1 < ntiles) { tile_scores(1, t + 1); tile_output(1); }
+    store_tile(0, t + 2, krA, vrA);
+    issue_tile(t + 4, krA, vrA);
     __syncthreads();
   }
 
@@ -902,8 +943,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
       for (int r4 = 0; r4 < 4; ++r4) {
         const int d = 32 * db + 8 * r4 + 4 * lh;
         *reinterpret_cast<float4*>(o + d) =
-            make_float4(oacc[db][4 * r4] * kRtzFix, oacc[db][4 * r4 + 1] * kRtzFix, oacc[db][4 * r4 + 2] * kRtzFix,
-                        oacc[db][4 * r4 + 3] * kRtzFix);
+            make_float4(oacc[db][4 * r4] * kRtzFix, oacc[db][4 * r4 + 1] * kRtzFix,
+                        oacc[db][4 * r4 + 2] * kRtzFix, oacc[db][4 * r4 + 3] * kRtzFix);
       }
     if (lh == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(m_run, l_run);
   }
@@ -974,8 +1015,14 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   p.tau = 0;
   const int G = a.Hq / a.Hkv;
   const int max_rows = a.max_q * G;
-  if (max_rows <= 128) { p.kind = 0; p.rows_per_wg = 128; }
-  else if (a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
+  const int64_t max_tok0 = static_cast<int64_t>(a.max_pages) * a.page;
+  const bool ragged0 = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok0;
+  // Up to 64 query rows per KV head the token-split body streams as fast as memory delivers; beyond, its
+  // waves (one per 32-row block, each staging every tile for itself) are bound by their own staging and the
+  // row-split body, whose waves share each staged tile, is ahead on batches of like lengths (96 rows per KV
+  // head: 4.2 against 2.6 TB/s).  Ragged batches keep the token-split body and its sorted work list.
+  if (max_rows <= 64 || (max_rows <= 128 && ragged0 && a.B <= kPlanMaxB)) { p.kind = 0; p.rows_per_wg = 128; }
+  else if (max_rows <= 128 || a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
   else { p.kind = 2; p.rows_per_wg = 256; }
   const long force_kind = dev_knob("SPECV_ATTN_KIND", -1);            // force a kernel family
   if (force_kind == 1) { p.kind = 1; p.rows_per_wg = 128; }
@@ -991,7 +1038,7 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   // limits allow: (a) about one workgroup per compute unit should exist, (b) one wave should not
   // stream more than ~40 tiles in sequence, or the longest workgroup sets the kernel's duration.
   const long jobs_knob = dev_knob("SPECV_ATTN_JOBS", 0);
-  const int64_t jobs_target = jobs_knob > 0 ? jobs_knob : 256;
+  const int64_t jobs_target = jobs_knob > 0 ? jobs_knob : (p.kind == 1 ? 512 : 256);   // 4-wave bodies: two per compute unit
   int64_t chunk = (tok * a.Hkv * p.row_groups + jobs_target - 1) / jobs_target;
   if (token_split && jobs_knob <= 0) {
     // waves that share one query block (pair) and therefore split its tiles
@@ -1013,7 +1060,7 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   // which only pays when lengths differ: the caller's total-token hint against batch x longest
   // request says whether they do.
   const bool ragged = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok;
-  int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 36 : 0;
+  int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 48 : 0;   // with the alternating hand-out below: 44-56 measured best
   const long tau_knob = dev_knob("SPECV_ATTN_TAU", -1);   // 0: grid-mapped launch
   if (token_split && a.B <= kPlanMaxB && tau_knob >= 0 && tau_knob <= 255) tau = static_cast<int>(tau_knob);
   if (jobs_knob > 0) tau = 0;
@@ -1038,7 +1085,8 @@ size_t attn_workspace_bytes(const AttnArgs& a, const AttnPlan& p) {
 const char* attn_plan_name(const AttnPlan& p) {
   if (p.kind == 0) return p.tau > 0 ? "attn_stream_list_kernel (token-split body, device-built work list sorted by length)"
                                     : "attn_stream_kernel (token-split body, one workgroup per request x KV head x context chunk)";
-  return p.kind == 1 ? "attn_rows_kernel<4 waves> (row-split body)" : "attn_rows_kernel<8 waves> (row-split body)";
+  if (p.kind == 1) return "attn_rows_kernel<4 waves> (row-split body)";
+  return "attn_rows_kernel<8 waves> (row-split body, 256 query rows per workgroup)";
 }
 
 template <int D>
