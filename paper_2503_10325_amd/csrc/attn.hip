@@ -68,6 +68,8 @@ struct AttnParams {
   float2* ws_ml;     // [rows, max_chunks] (max in log2 units, sum)
   int B, Hq, Hkv, G, max_pages, chunk_tokens, max_chunks;
   int tau;           // > 0: a request is cut so that one wave streams at most tau tiles per work item
+  int list_rows_min; // > 0 (work list only): requests with this many query rows per KV head use the row-split body
+  int list_rows_units;  // eighths of a work-list unit that 32 tokens of such a request cost
   float c;           // scale * log2(e)
   int out_f32;
 };
@@ -125,6 +127,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 
 // Waves of a token-split workgroup that share one query block, for R <= 128 query rows.
+// A zero the compiler cannot see through.  Added to the thread id at the top of a work item's body, it ties the
+// per-lane constants of that body (lane offsets, LDS addresses) to the item: in a kernel that loops over items
+// of two different bodies they would otherwise be hoisted out of the loop and held in registers across both.
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+s"(z));
+  return z;
+}
+
 __device__ __forceinline__ int stream_nslice(int R) {
   const int nqb = min(4, (R + 31) / 32);
   return nqb <= 1 ? 4 : (nqb <= 2 ? 2 : 1);
@@ -133,12 +144,25 @@ __device__ __forceinline__ int stream_nslice(int R) {
 // Number of context chunks of a request with L tokens and n draft nodes.  The token-split,
 // sorted-work-list launch (tau > 0) cuts by the number of tiles one wave streams; the other
 // launches cut by tokens.  The attention kernels and the combine kernel all use this function.
+// Work-list launches run requests with at least P.list_rows_min query rows per KV head through the row-split
+// body (its waves share every staged tile; the token-split body stages a tile once per 32-row block).
+__device__ __forceinline__ bool list_uses_rows(const AttnParams& P, int n) {
+  return P.list_rows_min > 0 && n * P.G >= P.list_rows_min;
+}
+
+// Length of a request in the work list's unit, the 32-token tiles one wave of the token-split body streams.
+// For the row-split body 32 tokens count P.list_rows_units eighths of a unit: batches of equal requests
+// measure 5/8 (a 64-token tile takes 1.25 times a 32-token one), ragged batches of both kinds run best
+// with 3/8 to 4/8; the host passes 4.
+__device__ __forceinline__ int request_units(const AttnParams& P, int L, int n) {
+  const int tiles = (L + kTile - 1) / kTile;
+  if (list_uses_rows(P, n)) return (tiles * P.list_rows_units + 7) / 8;
+  const int nslice = stream_nslice(min(n * P.G, 128));
+  return (tiles + nslice - 1) / nslice;
+}
+
 __device__ __forceinline__ int request_chunks(const AttnParams& P, int L, int n) {
-  if (P.tau > 0) {
-    const int nslice = stream_nslice(min(n * P.G, 128));
-    const int per_wave = ((L + kTile - 1) / kTile + nslice - 1) / nslice;
-    return min(max(1, (per_wave + P.tau - 1) / P.tau), P.max_chunks);
-  }
+  if (P.tau > 0) return min(max(1, (request_units(P, L, n) + P.tau - 1) / P.tau), P.max_chunks);
   return max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
 }
 
@@ -153,7 +177,8 @@ __device__ __forceinline__ int request_chunks(const AttnParams& P, int L, int n)
 template <int D>
 __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg) {
   using C = AttnCfg<D>;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = static_cast<int>(threadIdx.x) + opaque_zero(), lane = tid & 63, wave = tid >> 6;
+  __builtin_assume(tid >= 0 && tid < kAttnThreads);
   const int ln = lane & 31, lh = lane >> 5;
 
   const int q0 = P.q_offsets[b];
@@ -490,67 +515,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams
   stream_item<D>(P, smem, blockIdx.z, blockIdx.y, blockIdx.x % P.max_chunks, blockIdx.x / P.max_chunks);
 }
 
-// Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
-// is two workgroups per compute unit; every workgroup derives the same list of work items
-// (request, chunk, KV head) from the lengths on the device, ordered by decreasing number of tiles
-// a wave streams per item, and takes items blockIdx.x, blockIdx.x + gridDim.x, ...: long items
-// start first, short ones fill the tail, and no workgroup is launched for chunks that do not exist.
 constexpr int kPlanMaxB = 128;
-
-template <int D>
-__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnParams P) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int sh_first[kPlanMaxB + 1];        // first item of the request at sorted position s
-  __shared__ unsigned char sh_order[kPlanMaxB];  // request at sorted position s
-  const int tid = threadIdx.x;
-  int* key = reinterpret_cast<int*>(smem);       // scratch in the tile memory, dead before the first item
-  int* cnt = key + kPlanMaxB;
-  int my_key = -1, my_cnt = 0;
-  if (tid < P.B) {
-    int n = P.q_offsets[tid + 1] - P.q_offsets[tid];
-    n = n > kMaxQ ? kMaxQ : n;
-    if (n > 0) {
-      const int L = P.ctx_len[tid] + n;
-      const int nch = request_chunks(P, L, n);
-      const int nslice = stream_nslice(min(n * P.G, 128));
-      const int per_wave = ((L + kTile - 1) / kTile + nslice - 1) / nslice;
-      my_key = (per_wave + nch - 1) / nch;       // tiles one wave streams per item of this request
-      my_cnt = nch * P.Hkv;
-    }
-  }
-  if (tid < kPlanMaxB) { key[tid] = my_key; cnt[tid] = my_cnt; }
-  __syncthreads();
-  if (tid < P.B) {
-    int rank = 0, first = 0;
-    for (int j = 0; j < P.B; ++j) {
-      const int kj = key[j];
-      const bool before = kj > my_key || (kj == my_key && j < tid);
-      rank += before ? 1 : 0;
-      first += before ? cnt[j] : 0;
-    }
-    sh_order[rank] = static_cast<unsigned char>(tid);
-    sh_first[rank] = first;
-    if (rank == P.B - 1) sh_first[P.B] = first + my_cnt;
-  }
-  __syncthreads();
-  const int total = sh_first[P.B];
-  // Round r hands out items r*G .. r*G+G-1 (G workgroups), in workgroup order on even rounds and in reverse
-  // on odd ones: the workgroup that got the longest item of one round gets the shortest of the next.
-  for (int round = 0;; ++round) {
-    const int slot = (round & 1) ? static_cast<int>(gridDim.x - 1 - blockIdx.x) : static_cast<int>(blockIdx.x);
-    const int item = round * static_cast<int>(gridDim.x) + slot;
-    if (item >= total) break;
-    int lo = 0, hi = P.B;                         // largest s with sh_first[s] <= item
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (sh_first[mid] <= item) lo = mid; else hi = mid;
-    }
-    const int b = sh_order[lo];
-    const int local = item - sh_first[lo];
-    stream_item<D>(P, smem, b, local % P.Hkv, local / P.Hkv, 0);
-    __syncthreads();                              // the tile memory is reused by the next item
-  }
-}
 
 // ----------------------------------------------------------------------------------
 // Row-split variant for requests with more than 32 query rows per KV head (GQA groups
@@ -577,15 +542,17 @@ struct RowsCfg {
   static_assert(kTpt == 4 || kTpt == 2, "unsupported tile/thread combination");
 };
 
+// One work item of the row-split body: (request b, KV head kvh, context chunk `chunk` of `nchunks`, row group
+// rg).  The request's context is cut into nchunks pieces of cb tokens (a multiple of the tile).  Every return
+// below is workgroup-uniform up to the last barrier.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(AttnParams P) {
+__device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg,
+                                          int nchunks, int cb) {
   using C = AttnCfg<D>;
   using RC = RowsCfg<D, NW>;
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = static_cast<int>(threadIdx.x) + opaque_zero(), lane = tid & 63, wave = tid >> 6;
+  __builtin_assume(tid >= 0 && tid < RC::kThreads);
   const int ln = lane & 31, lh = lane >> 5;
-  const int b = blockIdx.z, kvh = blockIdx.y;
-  const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
 
   const int q0 = P.q_offsets[b];
   int n = P.q_offsets[b + 1] - q0;
@@ -596,9 +563,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   const int R = n * P.G;
   const int row0 = rg * (32 * NW);
   if (row0 >= R) return;
-  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
   if (chunk >= nchunks) return;
-  const int cb = (((L + nchunks - 1) / nchunks) + RC::kT - 1) & ~(RC::kT - 1);
   const int t_begin = chunk * cb;
   if (t_begin >= L) return;                     // rounding the chunk up to whole tiles can empty the last one
   const int t_end = min(L, t_begin + cb);
@@ -890,22 +855,41 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   // same number of loads outstanding on every path, the wait before a store covers only the older register
   // set and leaves the newer one in flight.  A branch around an issue would make that wait a full drain.
   fetch_pages(0);
-  issue_tile(0, krA, vrA);
-  issue_tile(1, krB, vrB);
-  store_tile(0, 0, krA, vrA);
-  issue_tile(2, krA, vrA);
-  __syncthreads();
-  for (int t = 0; t < ntiles; t += 2) {
-    // LDS stage 0 holds tile t, set B tile t+1, set A tile t+2
-    if (active) { tile_scores(0, t); tile_output(0); }
-    store_tile(1, t + 1, krB, vrB);
-    issue_tile(t + 3, krB, vrB);
+  if constexpr (NW == 8) {
+    issue_tile(0, krA, vrA);
+    issue_tile(1, krB, vrB);
+    store_tile(0, 0, krA, vrA);
+    issue_tile(2, krA, vrA);
     __syncthreads();
-    // LDS stage 1 holds tile t+1, set A tile t+2, set B tile t+3
-    if (active && t + 1 < ntiles) { tile_scores(1, t + 1); tile_output(1); }
-    store_tile(0, t + 2, krA, vrA);
-    issue_tile(t + 4, krA, vrA);
+    for (int t = 0; t < ntiles; t += 2) {
+      // LDS stage 0 holds tile t, set B tile t+1, set A tile t+2
+      if (active) { tile_scores(0, t); tile_output(0); }
+      store_tile(1, t + 1, krB, vrB);
+      issue_tile(t + 3, krB, vrB);
+      __syncthreads();
+      // LDS stage 1 holds tile t+1, set A tile t+2, set B tile t+3
+      if (active && t + 1 < ntiles) { tile_scores(1, t + 1); tile_output(1); }
+      store_tile(0, t + 2, krA, vrA);
+      issue_tile(t + 4, krA, vrA);
+      __syncthreads();
+    }
+  } else {
+    // Four waves, two workgroups per compute unit: one register set (one tile of loads in flight per
+    // workgroup; the other workgroup covers the rest of the latency), which leaves the registers for it.
+    issue_tile(0, krA, vrA);
+    store_tile(0, 0, krA, vrA);
+    issue_tile(1, krA, vrA);
     __syncthreads();
+    for (int t = 0; t < ntiles; t += 2) {
+      if (active) { tile_scores(0, t); tile_output(0); }
+      store_tile(1, t + 1, krA, vrA);
+      issue_tile(t + 2, krA, vrA);
+      __syncthreads();
+      if (active && t + 1 < ntiles) { tile_scores(1, t + 1); tile_output(1); }
+      store_tile(0, t + 2, krA, vrA);
+      issue_tile(t + 3, krA, vrA);
+      __syncthreads();
+    }
   }
 
   // ---- write this wave's rows ----
@@ -947,6 +931,86 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
                         oacc[db][4 * r4 + 2] * kRtzFix, oacc[db][4 * r4 + 3] * kRtzFix);
       }
     if (lh == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(m_run, l_run);
+  }
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(AttnParams P) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int b = blockIdx.z;
+  const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
+  int n = P.q_offsets[b + 1] - P.q_offsets[b];
+  n = n > kMaxQ ? kMaxQ : n;
+  const int L = P.ctx_len[b] + n;
+  const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
+  const int cb = (((L + nchunks - 1) / nchunks) + RowsCfg<D, NW>::kT - 1) & ~(RowsCfg<D, NW>::kT - 1);
+  rows_item<D, NW>(P, smem, b, blockIdx.y, chunk, rg, nchunks, cb);
+}
+
+// Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
+// is two workgroups per compute unit; every workgroup derives the same list of work items
+// (request, chunk, KV head) from the lengths on the device, ordered by decreasing number of tiles
+// a wave streams per item, and takes items blockIdx.x, blockIdx.x + gridDim.x, ...: long items
+// start first, short ones fill the tail, and no workgroup is launched for chunks that do not exist.
+// An item runs the token-split body or, for requests with many query rows, the row-split body.
+template <int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnParams P) {
+  using RC = RowsCfg<D, 4>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int sh_first[kPlanMaxB + 1];        // first item of the request at sorted position s
+  __shared__ unsigned char sh_order[kPlanMaxB];  // request at sorted position s
+  const int tid = threadIdx.x;
+  int* key = reinterpret_cast<int*>(smem);       // scratch in the tile memory, dead before the first item
+  int* cnt = key + kPlanMaxB;
+  int my_key = -1, my_cnt = 0;
+  if (tid < P.B) {
+    int n = P.q_offsets[tid + 1] - P.q_offsets[tid];
+    n = n > kMaxQ ? kMaxQ : n;
+    if (n > 0) {
+      const int L = P.ctx_len[tid] + n;
+      const int nch = request_chunks(P, L, n);
+      my_key = (request_units(P, L, n) + nch - 1) / nch;   // length of one item of this request
+      my_cnt = nch * P.Hkv;
+    }
+  }
+  if (tid < kPlanMaxB) { key[tid] = my_key; cnt[tid] = my_cnt; }
+  __syncthreads();
+  if (tid < P.B) {
+    int rank = 0, first = 0;
+    for (int j = 0; j < P.B; ++j) {
+      const int kj = key[j];
+      const bool before = kj > my_key || (kj == my_key && j < tid);
+      rank += before ? 1 : 0;
+      first += before ? cnt[j] : 0;
+    }
+    sh_order[rank] = static_cast<unsigned char>(tid);
+    sh_first[rank] = first;
+    if (rank == P.B - 1) sh_first[P.B] = first + my_cnt;
+  }
+  __syncthreads();
+  const int total = sh_first[P.B];
+  // Round r hands out items r*G .. r*G+G-1 (G workgroups), in workgroup order on even rounds and in reverse
+  // on odd ones: the workgroup that got the longest item of one round gets the shortest of the next.
+  for (int round = 0;; ++round) {
+    const int slot = (round & 1) ? static_cast<int>(gridDim.x - 1 - blockIdx.x) : static_cast<int>(blockIdx.x);
+    const int item = round * static_cast<int>(gridDim.x) + slot;
+    if (item >= total) break;
+    int lo = 0, hi = P.B;                         // largest s with sh_first[s] <= item
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (sh_first[mid] <= item) lo = mid; else hi = mid;
+    }
+    const int b = sh_order[lo];
+    const int local = item - sh_first[lo];
+    int n = P.q_offsets[b + 1] - P.q_offsets[b];
+    n = n > kMaxQ ? kMaxQ : n;
+    const int L = P.ctx_len[b] + n;
+    const int nch = request_chunks(P, L, n);
+    const int cb = (((L + nch - 1) / nch) + RC::kT - 1) & ~(RC::kT - 1);
+    // (a chunk longer than the row-split body's page table in LDS stays with the token-split body)
+    if (list_uses_rows(P, n) && cb <= RC::kMaxChunkPages * kPage) rows_item<D, 4>(P, smem, b, local % P.Hkv, local / P.Hkv, 0, nch, cb);
+    else stream_item<D>(P, smem, b, local % P.Hkv, local / P.Hkv, 0);
+    __syncthreads();                              // the tile memory is reused by the next item
   }
 }
 
@@ -1083,7 +1147,7 @@ size_t attn_workspace_bytes(const AttnArgs& a, const AttnPlan& p) {
 }
 
 const char* attn_plan_name(const AttnPlan& p) {
-  if (p.kind == 0) return p.tau > 0 ? "attn_stream_list_kernel (token-split body, device-built work list sorted by length)"
+  if (p.kind == 0) return p.tau > 0 ? "attn_stream_list_kernel (device-built work list sorted by length; token-split body, row-split body from 65 query rows per KV head)"
                                     : "attn_stream_kernel (token-split body, one workgroup per request x KV head x context chunk)";
   if (p.kind == 1) return "attn_rows_kernel<4 waves> (row-split body)";
   return "attn_rows_kernel<8 waves> (row-split body, 256 query rows per workgroup)";
@@ -1098,10 +1162,12 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
   static std::atomic<uint64_t> attr_done{0};
   if (set_lds_once(&attn_stream_kernel<D>, kTiles, attr_done) != 0) return -6;
   if (plan.tau > 0) {
+    // both bodies run in this kernel: the tile memory of the larger one
+    constexpr size_t kListLds = kTiles > static_cast<size_t>(RowsCfg<D, 4>::kLds) ? kTiles : static_cast<size_t>(RowsCfg<D, 4>::kLds);
     static std::atomic<uint64_t> list_attr_done{0};
-    if (set_lds_once(&attn_stream_list_kernel<D>, kTiles, list_attr_done) != 0) return -6;
+    if (set_lds_once(&attn_stream_list_kernel<D>, kListLds, list_attr_done) != 0) return -6;
     const int n_cu = current_device_cus();
-    hipLaunchKernelGGL((attn_stream_list_kernel<D>), dim3(2 * n_cu), dim3(kAttnThreads), kTiles, stream, P);
+    hipLaunchKernelGGL((attn_stream_list_kernel<D>), dim3(2 * n_cu), dim3(kAttnThreads), kListLds, stream, P);
     return hipGetLastError() == hipSuccess ? 0 : -6;
   }
   dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
@@ -1133,6 +1199,9 @@ int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
                                     ((rows * plan.max_chunks * sizeof(float2) + 255) / 256) * 256);
   P.B = a.B; P.Hq = a.Hq; P.Hkv = a.Hkv; P.G = a.Hq / a.Hkv; P.max_pages = a.max_pages;
   P.chunk_tokens = plan.chunk_tokens; P.max_chunks = plan.max_chunks; P.tau = plan.tau;
+  // work list: from 65 query rows per KV head (three 32-row blocks) on, a request runs the row-split body
+  P.list_rows_min = plan.tau > 0 ? static_cast<int>(dev_knob("SPECV_ATTN_LIST_ROWS", 65)) : 0;
+  P.list_rows_units = static_cast<int>(dev_knob("SPECV_ATTN_ROWS_UNITS", 4));
   P.c = a.scale * kLog2e;
   P.out_f32 = (a.out_dtype == kF32);
   int rc;

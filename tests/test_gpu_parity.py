@@ -32,8 +32,14 @@ ATTN_CASES = {
                                draft=("tree", (3, 2, 2), 17)),
     "ragged_gqa8": W.scaled(C["c4_llama70b_serving"], batch=7, n_q_heads=16, n_kv_heads=2,
                             ctx=("lognormal", 300, 0.8, 17, 1500)),
+    # ragged lengths with 16 to 128 query rows per KV head: the work list mixes both attention bodies, and the
+    # long requests of either kind are cut into several chunks
+    "ragged_rows_mixed": W.scaled(C["c4_llama70b_serving"], batch=6, n_q_heads=16, n_kv_heads=2,
+                                  ctx=("lognormal", 2500, 0.9, 30, 9000), draft=("linear_uniform", 2, 16)),
     "d64_gqa2": W.scaled(C["c0_tiny"], batch=3, n_q_heads=4, n_kv_heads=2, ctx=("uniform", 5, 400),
                          draft=("linear_uniform", 1, 9)),
+    "d64_rows_mixed": W.scaled(C["c0_tiny"], batch=5, n_q_heads=16, n_kv_heads=2, ctx=("uniform", 5, 3000),
+                               draft=("linear_uniform", 2, 14)),
     "ctx_zero": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=1, ctx=("fixed", 0), draft=("linear", 5)),
     "page_boundary": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=2, ctx=("fixed", 56), draft=("linear", 8)),
 }
@@ -55,7 +61,7 @@ def test_attention_matches_oracle(rt, name):
     assert np.abs(lse - ref_lse).max() < 2e-2, f"{name}: lse err {np.abs(lse - ref_lse).max()}"
 
 
-@pytest.mark.parametrize("name", ["ragged_gqa8", "d64_gqa2", "linear_multi_chunk", "tree_small_gqa"])
+@pytest.mark.parametrize("name", ["ragged_gqa8", "ragged_rows_mixed", "d64_rows_mixed", "d64_gqa2", "linear_multi_chunk", "tree_small_gqa"])
 @pytest.mark.parametrize("hint", ["none", "exact", "small"])
 def test_attention_launch_modes(rt, name, hint):
     """The total-token hint only steers how the work is cut (grid-mapped chunks when it is absent or
