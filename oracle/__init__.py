@@ -15,7 +15,8 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+# SPECV_ORACLE_LIB: another build of oracle.c to load instead (the sanitizer build, in its test)
+_LIB_PATH = os.environ.get("SPECV_ORACLE_LIB") or os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 BF16, F32 = 0, 1

@@ -715,7 +715,7 @@ const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
   if (!cluster) return "row_stats_kernel (all rows) + accept_walk_kernel (one workgroup per request, helper workgroups)";
   const ClusterPlan p = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
   return p.solo ? "accept_cluster_kernel (one workgroup per request, rows of the walked path only)"
-                : "accept_cluster_kernel (cluster of workgroups per request, register-resident row slices)";
+                : "accept_cluster_kernel (cluster of workgroups per request, row slices held in LDS)";
 }
 
 void launch_accept(const AcceptArgs& a, hipStream_t stream) {
