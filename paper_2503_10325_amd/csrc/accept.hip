@@ -3,13 +3,15 @@
 // 1 - o_i(x_i)/q_i(x_i); replacement from norm(max(0, o_i - q_i)); bonus token when
 // nothing is rejected), extended to sibling drafts of a tree by recursive rejection.
 //
-// Two kernels:
-//   row_stats_kernel    one workgroup per (row, vocab segment): segment maximum and
-//                       sum of 2^((l-m)c).  Pure streaming, HBM-bound.
-//   accept_walk_kernel  one master workgroup per request: the sequential walk; every full
-//                       pass over a row pair (residual mass, inverse-CDF search) is
-//                       spread over the workgroup's 16 waves and, for large vocabularies,
-//                       over the waves of up to three helper workgroups.
+// Kernels:
+//   row_stats_kernel      one workgroup per (row, vocab segment): segment maximum and
+//                         sum of 2^((l-m)c).  Pure streaming, HBM-bound.
+//   accept_walk_kernel    one master workgroup per request: the sequential walk; every full
+//                         pass over a row pair (residual mass, inverse-CDF search) is
+//                         spread over the workgroup's 16 waves and, for large vocabularies,
+//                         over the waves of up to three helper workgroups.
+//   accept_linear_kernel  linear drafts: the scalar tests repeated in every workgroup, the one
+//                         vocabulary-wide draw spread over several workgroups per request.
 #include "common.h"
 #include "kernels.h"
 
@@ -676,10 +678,312 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   for (int i = depth + 1 + tid; i < P.out_stride; i += kWalkThreads) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + i] = -1;
 }
 
+// ----------------------------------------------------------------------------------
+// Linear drafts (no parent array): a chain is rejected at most once, so after the scalar accept tests exactly one
+// vocabulary-wide distribution is left to draw from - max(0, p - q) of the rejected position, or p after the
+// last draft when nothing was rejected (Section 2.1).  accept_linear_kernel spreads that one pass over the chip:
+// a unit of whole 4096-class blocks per workgroup, U workgroups per request.  Every workgroup repeats the request's scalar
+// tests (a few dozen values from the row statistics), sums the weights of its unit and hands the sum over;
+// the workgroup that arrives last adds the U sums and draws the token.  Nobody waits for anybody.
+// ----------------------------------------------------------------------------------
+constexpr int kLinThreads = 512;
+constexpr int kLinWaves = kLinThreads / kWave;
+constexpr int kLinBlock = kLinThreads * 8;         // classes one sweep of a workgroup covers
+constexpr int kLinMaxBlocks = 4;                   // blocks per unit at most (their loads are issued together)
+constexpr int kLinMaxUnits = 512;                  // vocabularies up to 2M classes
+
+// most units a vocabulary can be cut into (one block each): sizes the workspace
+int linear_units(int V) { return (V + kLinBlock - 1) / kLinBlock; }
+
+// Classes per workgroup (whole blocks): about two workgroups per compute unit for the whole batch.
+static int linear_unit_classes(int B, int V, int n_cu) {
+  const int max_units = linear_units(V);
+  int U = (2 * n_cu + B - 1) / (B > 0 ? B : 1);
+  const int min_units = (max_units + kLinMaxBlocks - 1) / kLinMaxBlocks;
+  U = U < min_units ? min_units : (U > max_units ? max_units : U);
+  const int per = (V + U - 1) / U;
+  return (per + kLinBlock - 1) / kLinBlock * kLinBlock;
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptParams P, double* __restrict__ partial,
+                                                                    unsigned* __restrict__ arrived, int U, int unit_classes) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x / U, unit = blockIdx.x % U;
+  const int o = P.node_offsets[b];
+  int n = P.node_offsets[b + 1] - o;
+  n = n < 0 ? 0 : (n > kMaxNodes ? kMaxNodes : n);
+  const int64_t trow0 = static_cast<int64_t>(o) + b;
+  const int V = P.V;
+  const float c = P.c;
+  const bool q_is_probs = (P.q_kind == 1);
+
+  __shared__ float sh_tm[kMaxNodes + 1];
+  __shared__ double sh_tinvz[kMaxNodes + 1];
+  __shared__ float sh_qm[kMaxNodes];
+  __shared__ double sh_qinvz[kMaxNodes];
+  __shared__ int sh_tok[kMaxNodes], sh_qrow[kMaxNodes];
+  __shared__ double sh_px[kMaxNodes], sh_qx[kMaxNodes];
+  __shared__ float sh_u[kMaxNodes];
+  __shared__ float sh_zero[kMaxNodes];           // 1/R_k of lower levels: none exist at levels 0 and 1
+  __shared__ double sh_wsum[kLinWaves];
+  __shared__ double sh_part[kLinMaxUnits];
+  __shared__ int sh_last;
+  __shared__ int sh_cross[kLinWaves], sh_lastpos[kLinWaves];
+  __shared__ double sh_bw[kLinMaxBlocks][kLinWaves];
+
+  const double u_res = static_cast<double>(P.u_resample[b]);
+  // (1) node arrays (indices clamped: a bad entry gives a wrong answer for that request, never a wild read)
+  if (tid < n) {
+    sh_tok[tid] = min(max(P.draft_tokens[o + tid], 0), V - 1);
+    sh_qrow[tid] = min(max(P.q_row[o + tid], 0), P.n_q_rows - 1);
+    sh_u[tid] = P.u_accept[o + tid];
+  }
+  if (tid < kMaxNodes) sh_zero[tid] = 0.f;
+  __syncthreads();
+  // (2) the two logits of every drafted token (last wave) and the merged statistics of the n+1 target rows and
+  // the n draft rows (groups of 16 lanes, one segment each)
+  if (wave == kLinWaves - 1) {
+    if (lane < n) {
+      const int x = sh_tok[lane];
+      sh_px[lane] = static_cast<double>(load_logit(P.target, P.t_dtype, (trow0 + lane) * static_cast<int64_t>(V) + x));
+      sh_qx[lane] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, static_cast<int64_t>(sh_qrow[lane]) * V + x));
+    }
+  } else {
+    const int n_rows = (n + 1) + (q_is_probs ? 0 : n);
+    const int sl = tid & 15;
+    for (int ri = tid >> 4; ri < n_rows; ri += (kLinThreads - kWave) / 16) {
+      const int64_t srow = (ri <= n) ? trow0 + ri : static_cast<int64_t>(P.n_t_rows) + sh_qrow[ri - n - 1];
+      float m = -INFINITY;
+      for (int sg = sl; sg < P.nseg; sg += 16) m = fmaxf(m, P.stats[srow * P.nseg + sg].m);
+#pragma unroll
+      for (int d = 8; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 16));
+      double z = 0.0;
+      for (int sg = sl; sg < P.nseg; sg += 16) {
+        const SegStat st = P.stats[srow * P.nseg + sg];
+        if (st.m != -INFINITY) z += st.z * exp2(static_cast<double>(st.m - m) * static_cast<double>(c));
+      }
+#pragma unroll
+      for (int d = 8; d > 0; d >>= 1) z += __shfl_xor(z, d, 16);
+      if (sl == 0) {
+        if (ri <= n) { sh_tm[ri] = m; sh_tinvz[ri] = 1.0 / z; }
+        else { sh_qm[ri - n - 1] = m; sh_qinvz[ri - n - 1] = 1.0 / z; }
+      }
+    }
+  }
+  __syncthreads();
+  // (3) p(x_j), q(x_j) of every node in parallel (node j is tested against target row j, the distribution
+  // after nodes 0..j-1), then the chain itself on LDS data
+  __shared__ double sh_ratio[kMaxNodes];
+  if (tid < n) {
+    const double px = exp2((sh_px[tid] - static_cast<double>(sh_tm[tid])) * static_cast<double>(c)) * sh_tinvz[tid];
+    const double qx = q_is_probs ? sh_qx[tid]
+                                 : exp2((sh_qx[tid] - static_cast<double>(sh_qm[tid])) * static_cast<double>(c)) * sh_qinvz[tid];
+    double ratio;
+    if (qx > 0.0) ratio = px / qx;
+    else ratio = (px > 0.0) ? INFINITY : 0.0;
+    sh_ratio[tid] = ratio;
+  }
+  __syncthreads();
+  int depth = 0, rejected = -1;
+  for (int j = 0; j < n; ++j) {
+    if (static_cast<double>(sh_u[j]) < sh_ratio[j]) { ++depth; continue; }
+    rejected = j;
+    break;
+  }
+  if (unit == 0 && P.dbg_ratio)
+    for (int j = tid; j < n; j += kLinThreads)
+      P.dbg_ratio[o + j] = (rejected < 0 || j <= rejected) ? static_cast<float>(sh_ratio[j]) : __builtin_nanf("");
+  if (unit == 0) {          // everything but the drawn token is known here
+    for (int i = tid; i < P.out_stride; i += kLinThreads)
+      if (i != depth) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + i] = (i < depth) ? sh_tok[i] : -1;
+    if (tid == 0) {
+      P.accept_len[b] = depth;
+      if (P.stop_node) P.stop_node[b] = depth - 1;
+    }
+  }
+  WalkRows R;
+  R.t_base = P.target; R.t_dtype = P.t_dtype;
+  R.q_base = P.draft_q; R.q_dtype = P.q_dtype; R.q_is_probs = q_is_probs;
+  R.t_off = (trow0 + depth) * static_cast<int64_t>(V);
+  R.t_m = sh_tm[depth]; R.t_invz = sh_tinvz[depth];
+  R.have_q = rejected >= 0;
+  R.q_off = 0; R.q_m = 0.f; R.q_invz = 0.0;
+  int level = 0;
+  if (rejected >= 0) {
+    R.q_off = static_cast<int64_t>(sh_qrow[rejected]) * V;
+    if (!q_is_probs) { R.q_m = sh_qm[rejected]; R.q_invz = sh_qinvz[rejected]; }
+    level = 1;
+  }
+
+  // Weights of this thread's eight classes in each block of unit k (at most kLinMaxBlocks blocks, their loads
+  // issued together) and the per-block fp32 sums.  Identical arithmetic wherever it is called.
+  const int bpu = unit_classes / kLinBlock;         // blocks per unit, <= kLinMaxBlocks
+  const int nblocks = (V + kLinBlock - 1) / kLinBlock;
+  auto unit_weights = [&](int k, int L, float (&w)[kLinMaxBlocks][8], float (&lsf)[kLinMaxBlocks]) {
+    float lp[kLinMaxBlocks][8], lq[kLinMaxBlocks][8];
+#pragma unroll
+    for (int i = 0; i < kLinMaxBlocks; ++i) {
+      const int e0 = (k * bpu + i) * kLinBlock + tid * 8;
+      if (i < bpu && e0 < V) {
+        load8<VEC>(R.t_base, R.t_dtype, R.t_off, e0, V, lp[i]);
+        if (L > 0) load8<VEC>(R.q_base, R.q_dtype, R.q_off, e0, V, lq[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kLinMaxBlocks; ++i) {
+      const int e0 = (k * bpu + i) * kLinBlock + tid * 8;
+      lsf[i] = 0.f;
+      if (i < bpu && e0 < V) {
+        weights_from(R, lp[i], lq[i], min(8, V - e0), c, L, sh_zero, w[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lsf[i] += w[i][j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[i][j] = 0.f;
+      }
+    }
+  };
+  // total of a unit from the per-block sums: fp64 across blocks, lanes, waves in a fixed order
+  auto unit_total = [&](const float (&lsf)[kLinMaxBlocks]) -> double {
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < kLinMaxBlocks; ++i) acc += static_cast<double>(lsf[i]);
+    const double ws = wave_sum(acc);
+    __syncthreads();                  // earlier readers of sh_wsum are done
+    if (lane == 0) sh_wsum[wave] = ws;
+    __syncthreads();
+    double tot = 0.0;
+#pragma unroll
+    for (int v = 0; v < kLinWaves; ++v) tot += sh_wsum[v];
+    return tot;
+  };
+
+  float w[kLinMaxBlocks][8], lsf[kLinMaxBlocks];
+  unit_weights(unit, level, w, lsf);
+  const double mine = unit_total(lsf);
+  if (wave == 0) {                    // all lanes of wave 0 store the same words (no per-lane role around barriers)
+    st_dev(&partial[static_cast<int64_t>(b) * U + unit], mine);
+    wait_stores();
+    unsigned old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(&arrived[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    sh_last = (old == static_cast<unsigned>(U - 1));
+  }
+  __syncthreads();
+  if (!sh_last) return;
+
+  // ---- the last workgroup of the request: total, unit of the draw, block, class ----
+  for (int k = tid; k < U; k += kLinThreads) sh_part[k] = ld_dev(&partial[static_cast<int64_t>(b) * U + k]);
+  __syncthreads();
+  double total = 0.0;
+  for (int k = 0; k < U; ++k) total += sh_part[k];
+  if (level == 1 && !(total > 0.0)) {
+    // a residual without mass leaves the distribution as it was: draw from p (sums redone here; rare)
+    level = 0;
+    R.have_q = 0;
+    for (int k = 0; k < U; ++k) {
+      unit_weights(k, 0, w, lsf);
+      const double sk = unit_total(lsf);
+      __syncthreads();
+      if (tid == 0) sh_part[k] = sk;
+    }
+    __syncthreads();
+    total = 0.0;
+    for (int k = 0; k < U; ++k) total += sh_part[k];
+  }
+  const double target = u_res * total;
+  int ku = -1;
+  double before = 0.0;
+  for (int k = 0; k < U; ++k) {
+    const double sk = sh_part[k];
+    if (before + sk > target) { ku = k; break; }
+    before += sk;
+  }
+  if (ku < 0) {                       // rounding left no crossing: last unit with positive mass
+    for (int k = U - 1; k >= 0; --k) if (sh_part[k] > 0.0) { ku = k; break; }
+    if (ku < 0) ku = 0;
+    before = 0.0;
+    for (int k = 0; k < ku; ++k) before += sh_part[k];
+  }
+  // all blocks of that unit at once: per-block wave sums to LDS, then the block the draw falls in
+  unit_weights(ku, level, w, lsf);
+  __syncthreads();                    // earlier readers of sh_bw are done
+#pragma unroll
+  for (int i = 0; i < kLinMaxBlocks; ++i) {
+    const double ws = wave_sum(static_cast<double>(lsf[i]));
+    if (lane == 0) sh_bw[i][wave] = ws;
+  }
+  __syncthreads();
+  const int nb_unit = min(bpu, nblocks - ku * bpu);    // blocks this unit really has (>= 1)
+  int hit = nb_unit - 1;              // rounding left no crossing inside the unit: its last block
+  for (int i = 0; i < nb_unit; ++i) {
+    double sb = 0.0;
+#pragma unroll
+    for (int v = 0; v < kLinWaves; ++v) sb += sh_bw[i][v];
+    if (before + sb > target) { hit = i; break; }
+    if (i + 1 < nb_unit) before += sb;
+  }
+  // this thread's weights of the chosen block (selected without indexing the register arrays)
+  float wh[8];
+  float lsh = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) wh[j] = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLinMaxBlocks; ++i) {
+    if (i == hit) {
+      lsh = lsf[i];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) wh[j] = w[i][j];
+    }
+  }
+  const int e0 = (ku * bpu + hit) * kLinBlock + tid * 8;
+  int my_last = -1;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) if (wh[j] > 0.f) my_last = e0 + j;
+  const double ls = static_cast<double>(lsh);
+  double inc = ls;                    // inclusive scan of the lane sums inside the wave
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double tq = __shfl_up(inc, d, kWave);
+    if (lane >= d) inc += tq;
+  }
+  double run = before;                // mass ahead of this wave
+  for (int v = 0; v < wave; ++v) run += sh_bw[hit][v];
+  const unsigned long long cross = __ballot(run + inc > target);
+  int tok = -1;
+  {
+    double acc = run + inc - ls;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      acc += static_cast<double>(wh[j]);
+      if (tok < 0 && acc > target && wh[j] > 0.f) tok = e0 + j;
+    }
+    if (tok < 0) tok = my_last;       // rounding inside the lane: its last positive class
+  }
+  const int fl = cross ? __ffsll(static_cast<long long>(cross)) - 1 : 0;
+  const int cand = __shfl(tok, fl, kWave);
+  int ml = my_last;
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) ml = max(ml, __shfl_xor(ml, d, kWave));
+  if (lane == 0) { sh_cross[wave] = cross ? cand : -2; sh_lastpos[wave] = ml; }
+  __syncthreads();
+  if (tid == 0) {
+    int found = -1;
+    for (int v = 0; v < kLinWaves && found < 0; ++v)
+      if (sh_cross[v] != -2) found = sh_cross[v];          // first wave with a crossing (-1: its lane had no positive class)
+    if (found < 0) {                  // rounding across the block: its last positive class
+      for (int v = kLinWaves - 1; v >= 0 && found < 0; --v) if (sh_lastpos[v] >= 0) found = sh_lastpos[v];
+      if (found < 0) found = min(V - 1, (ku * bpu + hit) * kLinBlock);
+    }
+    if (depth < P.out_stride) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + depth] = found;
+  }
+}
+
 // Workspace: [row statistics][helper protocol: pass descriptors, hand-back slots (zeroed by the
 // statistics kernel)]
 struct AcceptLayout {
-  size_t words_off, n_zero_words, desc_off, part_off, msg_off, total;
+  size_t words_off, n_zero_words, desc_off, part_off, arrived_off, msg_off, lin_off, total;
 };
 
 static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
@@ -689,9 +993,11 @@ static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
   l.words_off = up(rows * stats_segments(V) * sizeof(SegStat));
   l.desc_off = l.words_off;
   l.part_off = l.desc_off + up(static_cast<size_t>(B) * sizeof(PassDesc));
-  l.msg_off = l.part_off + up(static_cast<size_t>(B) * kMaxHelpers * kWalkWaves * sizeof(PartSlot));
-  l.n_zero_words = (l.msg_off - l.words_off) / sizeof(unsigned);         // flags, descriptors and hand-back slots
-  l.total = l.msg_off + up(cluster_msg_bytes(B)) + 256;                  // messages of the cluster path
+  l.arrived_off = l.part_off + up(static_cast<size_t>(B) * kMaxHelpers * kWalkWaves * sizeof(PartSlot));
+  l.msg_off = l.arrived_off + up(static_cast<size_t>(B) * sizeof(unsigned));   // arrival counters of the linear-draft kernel
+  l.n_zero_words = (l.msg_off - l.words_off) / sizeof(unsigned);         // flags, descriptors, hand-back slots, counters
+  l.lin_off = l.msg_off + up(cluster_msg_bytes(B));                      // messages of the cluster path
+  l.total = l.lin_off + up(static_cast<size_t>(B) * linear_units(V) * sizeof(double)) + 256;   // unit sums of the linear-draft kernel
   return l;
 }
 
@@ -707,11 +1013,17 @@ static bool cluster_pays(int B, int V, int n_cu) {
   return units >= 8 && units <= 32 && static_cast<int64_t>(B) * units <= n_cu;
 }
 
+// Linear drafts take the statistics pass and accept_linear_kernel unless the caller asks for another path.
+static bool linear_path(const AcceptArgs& a) {
+  return a.parent == nullptr && (a.path == 0 || a.path == 3) && linear_units(a.V) <= kLinMaxUnits;
+}
+
 const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
   const bool vec = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
   const bool cluster_ok = vec && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
                           a.q_kind == 0 && !a.target_stats_ready;
-  const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && cluster_pays(a.B, a.V, n_cu)));
+  const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && a.parent != nullptr && cluster_pays(a.B, a.V, n_cu)));
+  if (!cluster && linear_path(a)) return "row_stats_kernel (all rows) + accept_linear_kernel (linear drafts: one vocabulary unit per workgroup, the last to arrive draws)";
   if (!cluster) return "row_stats_kernel (all rows) + accept_walk_kernel (one workgroup per request, helper workgroups)";
   const ClusterPlan p = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
   return p.solo ? "accept_cluster_kernel (one workgroup per request, rows of the walked path only)"
@@ -731,7 +1043,7 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
     const bool vec0 = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
     const bool cluster_ok = vec0 && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
                             a.q_kind == 0 && !a.target_stats_ready;
-    if (cluster_ok && (a.path == 2 || (a.path == 0 && cluster_pays(a.B, a.V, n_cu)))) {
+    if (cluster_ok && (a.path == 2 || (a.path == 0 && a.parent != nullptr && cluster_pays(a.B, a.V, n_cu)))) {
       const ClusterPlan plan = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
       launch_accept_cluster(a, plan, a.patience >= 0 ? a.patience : 4000, ws + lay.msg_off, stream);
       return;
@@ -763,6 +1075,18 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   P.stop_node = a.stop_node; P.dbg_ratio = a.dbg_ratio; P.stats = stats;
   P.desc = reinterpret_cast<PassDesc*>(ws + lay.desc_off);
   P.part = reinterpret_cast<PartSlot*>(ws + lay.part_off);
+  if (linear_path(a)) {
+    const int unit_classes = linear_unit_classes(a.B, a.V, n_cu);
+    const int U = (a.V + unit_classes - 1) / unit_classes;
+    P.helpers = 0; P.patience = 0; P.parent = nullptr;
+    double* partial = reinterpret_cast<double*>(ws + lay.lin_off);
+    unsigned* arrived = reinterpret_cast<unsigned*>(ws + lay.arrived_off);
+    const bool vec_l = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
+    const dim3 grid_l(static_cast<unsigned>(a.B) * U);
+    if (vec_l) hipLaunchKernelGGL((accept_linear_kernel<true>), grid_l, dim3(kLinThreads), 0, stream, P, partial, arrived, U, unit_classes);
+    else hipLaunchKernelGGL((accept_linear_kernel<false>), grid_l, dim3(kLinThreads), 0, stream, P, partial, arrived, U, unit_classes);
+    return;
+  }
   // Helpers pay when a pass is long against a hand-off between compute units (a few microseconds):
   // vocabularies of 64k classes and more; masters plus helpers stay within one workgroup per compute unit.
   int helpers = 0;

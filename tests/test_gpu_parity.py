@@ -8,7 +8,7 @@ torch = pytest.importorskip("torch")
 import oracle
 from paper_2503_10325_amd import workloads as W
 
-from gpu_util import ATTN_TOL, attn_rel_err, compare_accept, oracle_attn, ratio_err
+from gpu_util import ATTN_TOL, attn_rel_err, compare_accept, oracle_attn, ratio_err, visited_pattern_agrees
 
 pytestmark = pytest.mark.gpu
 
@@ -168,11 +168,12 @@ def _tuning(**kw):
     return sv.SpecAcceptTuning(**kw)
 
 
-@pytest.mark.parametrize("path", [0, 1, 2])
+@pytest.mark.parametrize("path", [0, 1, 2, 3])
 @pytest.mark.parametrize("name", list(ACCEPT_CASES))
 def test_accept_matches_oracle(rt, name, path):
     """path 0: the library's choice; 1: statistics pass over all rows + one walking workgroup per
-    request; 2: workgroup clusters that read only the walked rows (bf16 rows; other inputs fall back to 1)."""
+    request; 2: workgroup clusters that read only the walked rows (bf16 rows; other inputs fall back to 1);
+    3: statistics pass + the linear-draft kernel (trees fall back to 1)."""
     cfg, opt = ACCEPT_CASES[name]
     ai = W.make_accept_inputs(cfg, seed=4)
     got, ref = _run_accept(rt, cfg, ai, fp32=opt.get("fp32", False), tuning=_tuning(path=path) if path else None)
@@ -182,6 +183,52 @@ def test_accept_matches_oracle(rt, name, path):
     assert ties <= max(1, B // 4)
     assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
     assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
+
+
+LINEAR_CASES = {
+    # all accepted (draft rows = target rows): the draw comes from the row after the last draft
+    "all_accepted": (W.scaled(C["c1_llama2_7b"], batch=5, vocab=9000, q_src=("noise", 0.0)), {}),
+    # drafts far from the target: almost every request is rejected at its first node
+    "mostly_rejected": (W.scaled(C["c1_llama2_7b"], batch=7, vocab=12345, q_src=("independent", 3.0)), {}),
+    # a vocabulary of several units with a ragged last one (odd size: no 16-byte loads), ragged draft lengths
+    "units_ragged": (W.scaled(C["c4_llama70b_serving"], batch=9, vocab=20001, draft=("linear_uniform", 1, 12)), {}),
+    "one_unit_fp32": (W.scaled(C["c1_llama2_7b"], batch=4, vocab=777), {"fp32": True}),
+    "temperature_2": (W.scaled(C["c1_llama2_7b"], batch=6, vocab=8192, temperature=2.0), {}),
+}
+
+
+@pytest.mark.parametrize("name", list(LINEAR_CASES))
+def test_accept_linear_kernel_matches_oracle(rt, name):
+    """The linear-draft kernel (path 3): every workgroup repeats the scalar tests, one of them - whichever arrives
+    last - draws.  Same bar as every other path; and the walk kernel's results on the same inputs are the same
+    outside near-ties."""
+    cfg, opt = LINEAR_CASES[name]
+    ai = W.make_accept_inputs(cfg, seed=9)
+    assert ai.st.parent is None
+    got, ref = _run_accept(rt, cfg, ai, fp32=opt.get("fp32", False), tuning=_tuning(path=3))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    print(f"{name}: near-ties {ties}/{B}, mean accept_len {ref['accept_len'].mean():.2f}")
+    assert not bad, f"{name}: requests {bad} differ outside near-ties"
+    assert ties <= max(1, B // 4)
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+    assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
+    assert visited_pattern_agrees(got, ref, ai.st.node_offsets)
+    walk, _ = _run_accept(rt, cfg, ai, fp32=opt.get("fp32", False), tuning=_tuning(path=1))
+    bad2, _, _ = compare_accept(walk, ref, ai.st.n)
+    assert not bad2
+    assert np.array_equal(got["stop_node"], walk["stop_node"]) or ties > 0
+
+
+def test_accept_linear_kernel_probability_drafts(rt):
+    """Draft rows given as probabilities (SPEC_Q_PROBS) through the linear-draft kernel."""
+    cfg = W.scaled(C["c1_llama2_7b"], batch=6, vocab=6000)
+    ai = W.make_accept_inputs(cfg, seed=10)
+    logits = W.bf16_bits_to_f32(ai.draft_q).astype(np.float64) / cfg.temperature
+    probs = np.exp(logits - logits.max(axis=1, keepdims=True))
+    probs = (probs / probs.sum(axis=1, keepdims=True)).astype(np.float32)
+    got, ref = _run_accept(rt, cfg, ai, fp32=True, q_kind=1, draft_q=probs, tuning=_tuning(path=3))
+    bad, ties, B = compare_accept(got, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
 
 
 # (levels, slices) of the cluster path; 0 = the library's choice.  Vocabulary 128256 = 16 units of 8192 logits:
