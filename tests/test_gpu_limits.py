@@ -85,6 +85,52 @@ def test_accept_largest_vocabulary(rt):
         assert np.array_equal(gr[key], want[key]), key
 
 
+@pytest.mark.parametrize("shape,path", [("linear", 3), ("linear", 1), ("tree", 1), ("tree", 2)])
+def test_accept_clamps_indices_read_from_device_memory(rt, shape, path):
+    """Draft tokens, q_row entries and parents live in device memory the host layer cannot check.  Every kernel
+    clamps them before it uses them as an index (token to [0, V), q_row to [0, n_q_rows), a parent outside
+    [-1, j) to -1), so a corrupt entry changes that request's answer and nothing else: the result equals the
+    oracle's on the clamped arrays."""
+    from paper_2503_10325_amd import binding as sv
+    if shape == "linear":
+        cfg = W.scaled(C["c1_llama2_7b"], batch=6, vocab=5000)
+    else:
+        cfg = W.scaled(C["c2_tree_llama3_8b"], batch=4, vocab=8192, draft=("tree", (3, 2, 2), 17))
+    ai = W.make_accept_inputs(cfg, seed=21)
+    V, nq = cfg.vocab, ai.draft_q.shape[0]
+    rng = np.random.default_rng(5)
+    toks, qrow = ai.draft_tokens.copy(), ai.q_row.copy()
+    hit = rng.choice(len(toks), size=max(3, len(toks) // 5), replace=False)
+    toks[hit[0::3]] = -7
+    toks[hit[1::3]] = V + 9
+    qrow[hit[2::3]] = nq + 3
+    qrow[hit[0]] = -1
+    st = ai.st
+    parent = None
+    if st.parent is not None:
+        parent = st.parent.copy()
+        local = np.concatenate([np.arange(n) for n in st.n])
+        roots = np.flatnonzero(parent == -1)          # children of the prefix: clamping leaves the tree as it was
+        bad = rng.choice(roots, size=4, replace=False)
+        parent[bad[:2]] = local[bad[:2]] + 1          # not an earlier node
+        parent[bad[2:]] = -9
+        st = W.DraftStructure(st.n, st.node_offsets, parent, st.ctx_len)
+    c_toks, c_qrow = np.clip(toks, 0, V - 1), np.clip(qrow, 0, nq - 1)
+    c_parent = None
+    if parent is not None:
+        local = np.concatenate([np.arange(n) for n in st.n])
+        c_parent = np.where((parent < -1) | (parent >= local), -1, parent).astype(np.int32)
+    ref = oracle.accept(st.node_offsets, c_parent, c_toks, ai.target_logits, ai.draft_q, c_qrow, ai.u_accept,
+                        ai.u_resample, temperature=cfg.temperature)
+    dev = rt.DeviceAccept(st, ai.target_logits, ai.draft_q, qrow, toks, ai.u_accept, ai.u_resample,
+                          temperature=cfg.temperature)
+    dev.run(tuning=sv.SpecAcceptTuning(path=path))
+    got = dev.results()
+    # accepted tokens are reported as given (clamped): compare on the clamped arrays
+    bad_req, ties, B = compare_accept(got, ref, st.n)
+    assert not bad_req and ties <= 1
+
+
 def test_accept_vocabulary_above_the_limit_is_refused(rt):
     from paper_2503_10325_amd import binding as sv
     t = torch.zeros(8, dtype=torch.int32, device="cuda")
