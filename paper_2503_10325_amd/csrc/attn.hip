@@ -175,17 +175,15 @@ __device__ __forceinline__ int request_chunks(const AttnParams& P, int L, int n)
 // One work item: (request b, KV head kvh, context chunk, row group rg).  Every return below is
 // workgroup-uniform.
 template <int D>
-__device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg) {
+__device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg,
+                                            int q0, int n, int ctx) {
   using C = AttnCfg<D>;
   const int tid = static_cast<int>(threadIdx.x) + opaque_zero(), lane = tid & 63, wave = tid >> 6;
   __builtin_assume(tid >= 0 && tid < kAttnThreads);
   const int ln = lane & 31, lh = lane >> 5;
 
-  const int q0 = P.q_offsets[b];
-  int n = P.q_offsets[b + 1] - q0;
-  n = n > kMaxQ ? kMaxQ : n;
+  // (q0, n, ctx: first query row, number of query nodes (already capped at kMaxQ) and context length of request b)
   if (n <= 0) return;
-  const int ctx = P.ctx_len[b];
   const int L = ctx + n;
   const int R = n * P.G;
   const int row0 = rg * 128;
@@ -512,7 +510,11 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
 template <int D>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_kernel(AttnParams P) {
   extern __shared__ __align__(16) unsigned char smem[];
-  stream_item<D>(P, smem, blockIdx.z, blockIdx.y, blockIdx.x % P.max_chunks, blockIdx.x / P.max_chunks);
+  const int b = blockIdx.z;
+  const int q0 = P.q_offsets[b];
+  int n = P.q_offsets[b + 1] - q0;
+  n = n > kMaxQ ? kMaxQ : n;
+  stream_item<D>(P, smem, b, blockIdx.y, blockIdx.x % P.max_chunks, blockIdx.x / P.max_chunks, q0, n, P.ctx_len[b]);
 }
 
 constexpr int kPlanMaxB = 128;
@@ -536,7 +538,7 @@ struct RowsCfg {
   static constexpr int kVRows = 7 * 18 + D / 8;
   static constexpr int kVBytes = kVRows * kVStride;
   static constexpr int kStage = kKBytes + kVBytes;
-  static constexpr int kMaxChunkPages = 1024;              // a chunk spans at most 16384 tokens
+  static constexpr int kMaxChunkPages = NW == 8 ? 1024 : 512;   // a chunk spans at most 16384 (8192) tokens
   static constexpr int kPagePad = 32;                      // page-table entries kept past a chunk's last page
   static constexpr int kLds = 2 * kStage + 768 + (kMaxChunkPages + kPagePad) * 4;
   static_assert(kTpt == 4 || kTpt == 2, "unsupported tile/thread combination");
@@ -547,18 +549,14 @@ struct RowsCfg {
 // below is workgroup-uniform up to the last barrier.
 template <int D, int NW>
 __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg,
-                                          int nchunks, int cb) {
+                                          int nchunks, int cb, int q0, int n, int ctx) {
   using C = AttnCfg<D>;
   using RC = RowsCfg<D, NW>;
   const int tid = static_cast<int>(threadIdx.x) + opaque_zero(), lane = tid & 63, wave = tid >> 6;
   __builtin_assume(tid >= 0 && tid < RC::kThreads);
   const int ln = lane & 31, lh = lane >> 5;
 
-  const int q0 = P.q_offsets[b];
-  int n = P.q_offsets[b + 1] - q0;
-  n = n > kMaxQ ? kMaxQ : n;
   if (n <= 0) return;
-  const int ctx = P.ctx_len[b];
   const int L = ctx + n;
   const int R = n * P.G;
   const int row0 = rg * (32 * NW);
@@ -939,12 +937,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   extern __shared__ __align__(16) unsigned char smem[];
   const int b = blockIdx.z;
   const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
-  int n = P.q_offsets[b + 1] - P.q_offsets[b];
+  const int q0 = P.q_offsets[b];
+  int n = P.q_offsets[b + 1] - q0;
   n = n > kMaxQ ? kMaxQ : n;
-  const int L = P.ctx_len[b] + n;
+  const int ctx = P.ctx_len[b];
+  const int L = ctx + n;
   const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
   const int cb = (((L + nchunks - 1) / nchunks) + RowsCfg<D, NW>::kT - 1) & ~(RowsCfg<D, NW>::kT - 1);
-  rows_item<D, NW>(P, smem, b, blockIdx.y, chunk, rg, nchunks, cb);
+  rows_item<D, NW>(P, smem, b, blockIdx.y, chunk, rg, nchunks, cb, q0, n, ctx);
 }
 
 // Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
@@ -958,16 +958,23 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnP
   using RC = RowsCfg<D, 4>;
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int sh_first[kPlanMaxB + 1];        // first item of the request at sorted position s
-  __shared__ unsigned char sh_order[kPlanMaxB];  // request at sorted position s
+  // the request at sorted position s: first query row (below 2^16) | nodes << 16 | request << 24, and its context
+  // length: an item starts without a round trip to global memory for them
+  __shared__ int sh_meta[kPlanMaxB], sh_ctx[kPlanMaxB];
+  static_assert(kPlanMaxB <= 128 && kMaxQ <= 64, "request and node count share one word with the first query row");
   const int tid = threadIdx.x;
   int* key = reinterpret_cast<int*>(smem);       // scratch in the tile memory, dead before the first item
   int* cnt = key + kPlanMaxB;
-  int my_key = -1, my_cnt = 0;
+  int my_key = -1, my_cnt = 0, my_meta = 0, my_ctx = 0;
   if (tid < P.B) {
-    int n = P.q_offsets[tid + 1] - P.q_offsets[tid];
-    n = n > kMaxQ ? kMaxQ : n;
+    const int q0 = P.q_offsets[tid];
+    int n = P.q_offsets[tid + 1] - q0;
+    n = n > kMaxQ ? kMaxQ : (n < 0 ? 0 : n);
+    const int ctx = P.ctx_len[tid];
+    my_meta = q0 | (n << 16) | (tid << 24);
+    my_ctx = ctx;
     if (n > 0) {
-      const int L = P.ctx_len[tid] + n;
+      const int L = ctx + n;
       const int nch = request_chunks(P, L, n);
       my_key = (request_units(P, L, n) + nch - 1) / nch;   // length of one item of this request
       my_cnt = nch * P.Hkv;
@@ -983,7 +990,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnP
       rank += before ? 1 : 0;
       first += before ? cnt[j] : 0;
     }
-    sh_order[rank] = static_cast<unsigned char>(tid);
+    sh_meta[rank] = my_meta;
+    sh_ctx[rank] = my_ctx;
     sh_first[rank] = first;
     if (rank == P.B - 1) sh_first[P.B] = first + my_cnt;
   }
@@ -1000,16 +1008,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnP
       const int mid = (lo + hi) >> 1;
       if (sh_first[mid] <= item) lo = mid; else hi = mid;
     }
-    const int b = sh_order[lo];
+    const int meta = sh_meta[lo];
+    const int b = meta >> 24, q0 = meta & 0xffff, n = (meta >> 16) & 0xff, ctx = sh_ctx[lo];
     const int local = item - sh_first[lo];
-    int n = P.q_offsets[b + 1] - P.q_offsets[b];
-    n = n > kMaxQ ? kMaxQ : n;
-    const int L = P.ctx_len[b] + n;
+    const int L = ctx + n;
     const int nch = request_chunks(P, L, n);
     const int cb = (((L + nch - 1) / nch) + RC::kT - 1) & ~(RC::kT - 1);
     // (a chunk longer than the row-split body's page table in LDS stays with the token-split body)
-    if (list_uses_rows(P, n) && cb <= RC::kMaxChunkPages * kPage) rows_item<D, 4>(P, smem, b, local % P.Hkv, local / P.Hkv, 0, nch, cb);
-    else stream_item<D>(P, smem, b, local % P.Hkv, local / P.Hkv, 0);
+    if (list_uses_rows(P, n) && cb <= RC::kMaxChunkPages * kPage) rows_item<D, 4>(P, smem, b, local % P.Hkv, local / P.Hkv, 0, nch, cb, q0, n, ctx);
+    else stream_item<D>(P, smem, b, local % P.Hkv, local / P.Hkv, 0, q0, n, ctx);
     __syncthreads();                              // the tile memory is reused by the next item
   }
 }
@@ -1113,7 +1120,9 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   if (chunk < 256) chunk = 256;
   chunk = (chunk + gran - 1) / gran * gran;
   if (chunk > max_tok) chunk = (max_tok + gran - 1) / gran * gran;
-  if (!token_split && chunk > 16384) chunk = 16384;          // the row-split kernel keeps a chunk's page ids in LDS
+  // the row-split kernel keeps a chunk's page ids in LDS
+  const int64_t rows_chunk_cap = (p.kind == 2) ? 16384 : 8192;
+  if (!token_split && chunk > rows_chunk_cap) chunk = rows_chunk_cap;
   if (chunk < gran) chunk = gran;
   p.chunk_tokens = static_cast<int>(chunk);
   p.max_chunks = static_cast<int>((max_tok + chunk - 1) / chunk);
@@ -1124,9 +1133,10 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   // which only pays when lengths differ: the caller's total-token hint against batch x longest
   // request says whether they do.
   const bool ragged = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok;
-  int tau = (token_split && a.B <= kPlanMaxB && ragged) ? 48 : 0;   // with the alternating hand-out below: 44-56 measured best
+  // (the list kernel packs a request's first query row into 16 bits)
+  int tau = (token_split && a.B <= kPlanMaxB && a.total_q < 65536 && ragged) ? 48 : 0;   // with the alternating hand-out below: 44-56 measured best
   const long tau_knob = dev_knob("SPECV_ATTN_TAU", -1);   // 0: grid-mapped launch
-  if (token_split && a.B <= kPlanMaxB && tau_knob >= 0 && tau_knob <= 255) tau = static_cast<int>(tau_knob);
+  if (token_split && a.B <= kPlanMaxB && a.total_q < 65536 && tau_knob >= 0 && tau_knob <= 255) tau = static_cast<int>(tau_knob);
   if (jobs_knob > 0) tau = 0;
   if (tau > 0) {
     // most tiles one wave can have to stream: the longest request, shared by as many waves as the
@@ -1164,6 +1174,8 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
   if (plan.tau > 0) {
     // both bodies run in this kernel: the tile memory of the larger one
     constexpr size_t kListLds = kTiles > static_cast<size_t>(RowsCfg<D, 4>::kLds) ? kTiles : static_cast<size_t>(RowsCfg<D, 4>::kLds);
+    // two workgroups per compute unit: dynamic plus the kernel's static LDS (below 1664 bytes) within half of 160 KB
+    static_assert(kListLds + 1664 <= 80 * 1024, "the work-list kernel must fit twice into a compute unit's LDS");
     static std::atomic<uint64_t> list_attr_done{0};
     if (set_lds_once(&attn_stream_list_kernel<D>, kListLds, list_attr_done) != 0) return -6;
     const int n_cu = current_device_cus();
