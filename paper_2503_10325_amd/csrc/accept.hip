@@ -682,9 +682,10 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
 // Linear drafts (no parent array): a chain is rejected at most once, so after the scalar accept tests exactly one
 // vocabulary-wide distribution is left to draw from - max(0, p - q) of the rejected position, or p after the
 // last draft when nothing was rejected (Section 2.1).  accept_linear_kernel spreads that one pass over the chip:
-// a unit of whole 4096-class blocks per workgroup, U workgroups per request.  Every workgroup repeats the request's scalar
-// tests (a few dozen values from the row statistics), sums the weights of its unit and hands the sum over;
-// the workgroup that arrives last adds the U sums and draws the token.  Nobody waits for anybody.
+// a unit of one to four 4096-class blocks per workgroup, U workgroups per request.  Every workgroup repeats the
+// request's scalar tests (a few dozen values from the row statistics), sums the weights of its blocks and hands
+// the block sums over; the workgroup that arrives last adds them, finds the block of the draw and re-reads that
+// block alone for the class.  Nobody waits for anybody.
 // ----------------------------------------------------------------------------------
 constexpr int kLinThreads = 512;
 constexpr int kLinWaves = kLinThreads / kWave;
@@ -844,26 +845,31 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
       }
     }
   };
-  // total of a unit from the per-block sums: fp64 across blocks, lanes, waves in a fixed order
-  auto unit_total = [&](const float (&lsf)[kLinMaxBlocks]) -> double {
-    double acc = 0.0;
+  // per-block totals from the per-thread sums: fp64 across lanes and waves in a fixed order; in every thread
+  auto block_totals = [&](const float (&lsf)[kLinMaxBlocks], double (&tot)[kLinMaxBlocks]) {
+    __syncthreads();                  // earlier readers of sh_bw are done
 #pragma unroll
-    for (int i = 0; i < kLinMaxBlocks; ++i) acc += static_cast<double>(lsf[i]);
-    const double ws = wave_sum(acc);
-    __syncthreads();                  // earlier readers of sh_wsum are done
-    if (lane == 0) sh_wsum[wave] = ws;
+    for (int i = 0; i < kLinMaxBlocks; ++i) {
+      const double ws = wave_sum(static_cast<double>(lsf[i]));
+      if (lane == 0) sh_bw[i][wave] = ws;
+    }
     __syncthreads();
-    double tot = 0.0;
 #pragma unroll
-    for (int v = 0; v < kLinWaves; ++v) tot += sh_wsum[v];
-    return tot;
+    for (int i = 0; i < kLinMaxBlocks; ++i) {
+      tot[i] = 0.0;
+#pragma unroll
+      for (int v = 0; v < kLinWaves; ++v) tot[i] += sh_bw[i][v];
+    }
   };
 
   float w[kLinMaxBlocks][8], lsf[kLinMaxBlocks];
+  double tot[kLinMaxBlocks];
   unit_weights(unit, level, w, lsf);
-  const double mine = unit_total(lsf);
+  block_totals(lsf, tot);
   if (wave == 0) {                    // all lanes of wave 0 store the same words (no per-lane role around barriers)
-    st_dev(&partial[static_cast<int64_t>(b) * U + unit], mine);
+#pragma unroll
+    for (int i = 0; i < kLinMaxBlocks; ++i)
+      if (i < bpu && unit * bpu + i < nblocks) st_dev(&partial[static_cast<int64_t>(b) * nblocks + unit * bpu + i], tot[i]);
     wait_stores();
     unsigned old = 0;
     if (lane == 0) old = __hip_atomic_fetch_add(&arrived[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -873,71 +879,62 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
   __syncthreads();
   if (!sh_last) return;
 
-  // ---- the last workgroup of the request: total, unit of the draw, block, class ----
-  for (int k = tid; k < U; k += kLinThreads) sh_part[k] = ld_dev(&partial[static_cast<int64_t>(b) * U + k]);
+  // ---- the last workgroup of the request: total, block of the draw, class ----
+  for (int k = tid; k < nblocks; k += kLinThreads) sh_part[k] = ld_dev(&partial[static_cast<int64_t>(b) * nblocks + k]);
   __syncthreads();
   double total = 0.0;
-  for (int k = 0; k < U; ++k) total += sh_part[k];
+  for (int k = 0; k < nblocks; ++k) total += sh_part[k];
   if (level == 1 && !(total > 0.0)) {
     // a residual without mass leaves the distribution as it was: draw from p (sums redone here; rare)
     level = 0;
     R.have_q = 0;
     for (int k = 0; k < U; ++k) {
       unit_weights(k, 0, w, lsf);
-      const double sk = unit_total(lsf);
+      block_totals(lsf, tot);
       __syncthreads();
-      if (tid == 0) sh_part[k] = sk;
+      if (tid == 0) {
+#pragma unroll
+        for (int i = 0; i < kLinMaxBlocks; ++i)
+          if (i < bpu && k * bpu + i < nblocks) sh_part[k * bpu + i] = tot[i];
+      }
     }
     __syncthreads();
     total = 0.0;
-    for (int k = 0; k < U; ++k) total += sh_part[k];
+    for (int k = 0; k < nblocks; ++k) total += sh_part[k];
   }
   const double target = u_res * total;
-  int ku = -1;
+  int kb_hit = -1;
   double before = 0.0;
-  for (int k = 0; k < U; ++k) {
+  for (int k = 0; k < nblocks; ++k) {
     const double sk = sh_part[k];
-    if (before + sk > target) { ku = k; break; }
+    if (before + sk > target) { kb_hit = k; break; }
     before += sk;
   }
-  if (ku < 0) {                       // rounding left no crossing: last unit with positive mass
-    for (int k = U - 1; k >= 0; --k) if (sh_part[k] > 0.0) { ku = k; break; }
-    if (ku < 0) ku = 0;
+  if (kb_hit < 0) {                   // rounding left no crossing: last block with positive mass
+    for (int k = nblocks - 1; k >= 0; --k) if (sh_part[k] > 0.0) { kb_hit = k; break; }
+    if (kb_hit < 0) kb_hit = 0;
     before = 0.0;
-    for (int k = 0; k < ku; ++k) before += sh_part[k];
+    for (int k = 0; k < kb_hit; ++k) before += sh_part[k];
   }
-  // all blocks of that unit at once: per-block wave sums to LDS, then the block the draw falls in
-  unit_weights(ku, level, w, lsf);
-  __syncthreads();                    // earlier readers of sh_bw are done
-#pragma unroll
-  for (int i = 0; i < kLinMaxBlocks; ++i) {
-    const double ws = wave_sum(static_cast<double>(lsf[i]));
-    if (lane == 0) sh_bw[i][wave] = ws;
-  }
-  __syncthreads();
-  const int nb_unit = min(bpu, nblocks - ku * bpu);    // blocks this unit really has (>= 1)
-  int hit = nb_unit - 1;              // rounding left no crossing inside the unit: its last block
-  for (int i = 0; i < nb_unit; ++i) {
-    double sb = 0.0;
-#pragma unroll
-    for (int v = 0; v < kLinWaves; ++v) sb += sh_bw[i][v];
-    if (before + sb > target) { hit = i; break; }
-    if (i + 1 < nb_unit) before += sb;
-  }
-  // this thread's weights of the chosen block (selected without indexing the register arrays)
+  // that block alone: this thread's eight weights, the wave sums in LDS
   float wh[8];
   float lsh = 0.f;
+  {
+    const int eb = kb_hit * kLinBlock + tid * 8;
+    if (eb < V) {
+      weights8<VEC>(R, eb, V, c, level, sh_zero, wh);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) wh[j] = 0.f;
+      for (int j = 0; j < 8; ++j) lsh += wh[j];
+    } else {
 #pragma unroll
-  for (int i = 0; i < kLinMaxBlocks; ++i) {
-    if (i == hit) {
-      lsh = lsf[i];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) wh[j] = w[i][j];
+      for (int j = 0; j < 8; ++j) wh[j] = 0.f;
     }
+    const double ws = wave_sum(static_cast<double>(lsh));
+    __syncthreads();                  // earlier readers of sh_bw are done
+    if (lane == 0) sh_bw[0][wave] = ws;
+    __syncthreads();
   }
-  const int e0 = (ku * bpu + hit) * kLinBlock + tid * 8;
+  const int e0 = kb_hit * kLinBlock + tid * 8;
   int my_last = -1;
 #pragma unroll
   for (int j = 0; j < 8; ++j) if (wh[j] > 0.f) my_last = e0 + j;
@@ -949,7 +946,7 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
     if (lane >= d) inc += tq;
   }
   double run = before;                // mass ahead of this wave
-  for (int v = 0; v < wave; ++v) run += sh_bw[hit][v];
+  for (int v = 0; v < wave; ++v) run += sh_bw[0][v];
   const unsigned long long cross = __ballot(run + inc > target);
   int tok = -1;
   {
@@ -974,7 +971,7 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
       if (sh_cross[v] != -2) found = sh_cross[v];          // first wave with a crossing (-1: its lane had no positive class)
     if (found < 0) {                  // rounding across the block: its last positive class
       for (int v = kLinWaves - 1; v >= 0 && found < 0; --v) if (sh_lastpos[v] >= 0) found = sh_lastpos[v];
-      if (found < 0) found = min(V - 1, (ku * bpu + hit) * kLinBlock);
+      if (found < 0) found = min(V - 1, kb_hit * kLinBlock);
     }
     if (depth < P.out_stride) P.out_tokens[static_cast<int64_t>(b) * P.out_stride + depth] = found;
   }
@@ -997,7 +994,7 @@ static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
   l.msg_off = l.arrived_off + up(static_cast<size_t>(B) * sizeof(unsigned));   // arrival counters of the linear-draft kernel
   l.n_zero_words = (l.msg_off - l.words_off) / sizeof(unsigned);         // flags, descriptors, hand-back slots, counters
   l.lin_off = l.msg_off + up(cluster_msg_bytes(B));                      // messages of the cluster path
-  l.total = l.lin_off + up(static_cast<size_t>(B) * linear_units(V) * sizeof(double)) + 256;   // unit sums of the linear-draft kernel
+  l.total = l.lin_off + up(static_cast<size_t>(B) * linear_units(V) * sizeof(double)) + 256;   // block sums of the linear-draft kernel
   return l;
 }
 
