@@ -58,8 +58,8 @@ def parse_args():
     ap.add_argument("--accept-mode", choices=["sampling", "greedy"], default="sampling",
                     help="sampling: spec_accept (acceptance-rejection with residual resampling, the headline path); "
                          "greedy: spec_accept_greedy (the decoding rule of the paper's experiments)")
-    ap.add_argument("--accept-path", type=int, default=0, choices=[0, 1, 2, 3],
-                    help="0: the library's choice; 1: statistics pass over all rows + walk; 2: workgroup clusters; 3: statistics pass + linear-draft kernel")
+    ap.add_argument("--accept-path", type=int, default=0, choices=[0, 1, 2, 3, 4],
+                    help="0: the library's choice; 1: statistics pass over all rows + walk; 2: workgroup clusters; 3: statistics pass + linear-draft kernel; 4: the same, statistics up to each first rejection")
     ap.add_argument("--fuse-mode", choices=["argmax", "mixture"], default="argmax",
                     help="multi-drafter workloads: argmax = the paper's confidence rule (Eq. 4, the headline path); "
                          "mixture = confidence-weighted average of the drafters' distributions (Section 2.2), written "

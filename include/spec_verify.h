@@ -188,7 +188,8 @@ int32_t spec_accept(
 /* spec_accept with explicit launch choices, for tests and sweeps (same arguments, same results).
  * The library's choice: linear drafts (parent == NULL) take a statistics pass over all rows and then one
  * kernel that repeats the scalar accept tests in every workgroup and spreads the single vocabulary-wide
- * draw a chain needs over the chip (path 3).  Trees with bf16 logit rows (16-byte aligned, V a multiple
+ * draw a chain needs over the chip (path 3); large batches use a statistics pass that stops reading a
+ * request's rows at its first rejection (path 4).  Trees with bf16 logit rows (16-byte aligned, V a multiple
  * of 8) and a batch of at most one request per compute unit are walked by a cluster of workgroups per
  * request that keep slices of the walked rows in LDS and read no other row (path 2); other inputs take the
  * statistics pass followed by one walking workgroup per request (path 1).  No wait between workgroups is
@@ -196,7 +197,8 @@ int32_t spec_accept(
  * itself (0 = never wait); path 3 has no waits at all.  tuning == NULL is spec_accept. */
 typedef struct {
   int32_t path;      /* 0 = library's choice, 1 = statistics pass + walk, 2 = workgroup clusters, 3 = statistics
-                        pass + linear-draft kernel (2 and 3 fall back to 1 when the inputs do not qualify) */
+                        pass + linear-draft kernel, 4 = the same with a statistics pass that stops at each request's
+                        first rejection (2, 3, 4 fall back when the inputs do not qualify: 4 to 3, 3 and 2 to 1)   */
   int32_t levels;    /* path 2: rows of the walk looked at in one exchange, 0 = library's choice   */
   int32_t slices;    /* path 2: workgroups one row pair is cut over, 0 = library's choice          */
   int32_t patience;  /* < 0 = library's choice                                                     */

@@ -26,34 +26,11 @@ constexpr int kStatSeg = kStatThreads * kStatPerThread;         // 8192 logits p
 
 int stats_segments(int V) { return (V + kStatSeg - 1) / kStatSeg; }
 
+// (max, sum 2^((l - max) c)) of one 8192-logit segment of a row, by a workgroup of kStatThreads; the result is
+// valid in thread 0, for which the function returns true.
 template <bool VEC>
-__global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
-    const void* __restrict__ t_base, int t_dtype, int n_t_rows,
-    const void* __restrict__ q_base, int q_dtype, int n_q_rows,
-    int V, float c, int nseg, SegStat* __restrict__ stats, unsigned* __restrict__ zero_words, int n_zero,
-    const int32_t* __restrict__ q_row, int n_nodes) {
-  const int seg = blockIdx.x;
-  const int row = blockIdx.y;
-  // side job of the first workgroup: clear the flags the walk kernel's workgroups exchange
-  if (seg == 0 && row == 0)
-    for (int i = threadIdx.x; i < n_zero; i += kStatThreads) zero_words[i] = 0u;
-  const void* base = t_base;
-  int dtype = t_dtype;
-  int64_t r = row;
-  if (row >= n_t_rows) {
-    base = q_base; dtype = q_dtype; r = row - n_t_rows;
-    // With more draft rows than draft nodes (several drafters per position) most rows are nobody's:
-    // a row no node was drawn from (q_row, clamped as the walk clamps it) is not read at all.
-    if (q_row) {
-      int mine = 0;
-      for (int i = threadIdx.x; i < n_nodes; i += kStatThreads)
-        mine |= (min(max(q_row[i], 0), n_q_rows - 1) == static_cast<int>(r));
-      if (!__syncthreads_or(mine)) return;
-    }
-  }
-  const int64_t row_off = r * static_cast<int64_t>(V);
-  const int e_seg = seg * kStatSeg;
-
+__device__ __forceinline__ bool segment_stats(const void* __restrict__ base, int dtype, int64_t row_off, int e_seg, int V,
+                                              float c, float& M_out, double& Z_out) {
   float x[kStatPerThread];
 #pragma unroll
   for (int j = 0; j < kStatPerThread / 8; ++j) {
@@ -86,10 +63,43 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
   z = wave_sum(z);
   if (lane == 0) sh_z[wave] = z;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    double Z = 0.0;
+  double Z = 0.0;
 #pragma unroll
-    for (int w = 0; w < kStatThreads / kWave; ++w) Z += sh_z[w];
+  for (int w = 0; w < kStatThreads / kWave; ++w) Z += sh_z[w];
+  M_out = M;
+  Z_out = Z;
+  return threadIdx.x == 0;
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kStatThreads) void row_stats_kernel(
+    const void* __restrict__ t_base, int t_dtype, int n_t_rows,
+    const void* __restrict__ q_base, int q_dtype, int n_q_rows,
+    int V, float c, int nseg, SegStat* __restrict__ stats, unsigned* __restrict__ zero_words, int n_zero,
+    const int32_t* __restrict__ q_row, int n_nodes) {
+  const int seg = blockIdx.x;
+  const int row = blockIdx.y;
+  // side job of the first workgroup: clear the flags the walk kernel's workgroups exchange
+  if (seg == 0 && row == 0)
+    for (int i = threadIdx.x; i < n_zero; i += kStatThreads) zero_words[i] = 0u;
+  const void* base = t_base;
+  int dtype = t_dtype;
+  int64_t r = row;
+  if (row >= n_t_rows) {
+    base = q_base; dtype = q_dtype; r = row - n_t_rows;
+    // With more draft rows than draft nodes (several drafters per position) most rows are nobody's:
+    // a row no node was drawn from (q_row, clamped as the walk clamps it) is not read at all.
+    if (q_row) {
+      int mine = 0;
+      for (int i = threadIdx.x; i < n_nodes; i += kStatThreads)
+        mine |= (min(max(q_row[i], 0), n_q_rows - 1) == static_cast<int>(r));
+      if (!__syncthreads_or(mine)) return;
+    }
+  }
+  const int64_t row_off = r * static_cast<int64_t>(V);
+  float M;
+  double Z;
+  if (segment_stats<VEC>(base, dtype, row_off, seg * kStatSeg, V, c, M, Z)) {
     SegStat st;
     st.m = M; st.pad = 0.f; st.z = Z;
     stats[static_cast<int64_t>(row) * nseg + seg] = st;
@@ -246,6 +256,141 @@ template <typename T> __device__ __forceinline__ void st_dev(T* p, T v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ---- pieces shared by the kernels that take the scalar accept decisions --------------------------------
+// Merged (max, sum) of one logit row from its per-segment records, by a group of 16 lanes (lane sl of the
+// group takes segments sl, sl + 16, ...); the result is in every lane of the group.  DEV: read the records
+// with device-scope loads (they were written by other workgroups of the same kernel).  The arithmetic and
+// its order are the same for every caller, so every caller gets the same bits.
+template <bool DEV>
+__device__ __forceinline__ void merged_row_stats(const SegStat* __restrict__ rec, int nseg, float c, int sl,
+                                                 float& m_out, double& z_out) {
+  auto load = [&](int sg) -> SegStat {
+    if constexpr (DEV) {
+      const unsigned long long* w = reinterpret_cast<const unsigned long long*>(rec + sg);
+      const unsigned long long w0 = ld_dev(w), w1 = ld_dev(w + 1);
+      SegStat st;
+      st.m = __uint_as_float(static_cast<unsigned>(w0));
+      st.pad = 0.f;
+      st.z = __builtin_bit_cast(double, w1);
+      return st;
+    } else {
+      return rec[sg];
+    }
+  };
+  float m = -INFINITY;
+  for (int sg = sl; sg < nseg; sg += 16) m = fmaxf(m, load(sg).m);
+#pragma unroll
+  for (int d = 8; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 16));
+  double z = 0.0;
+  for (int sg = sl; sg < nseg; sg += 16) {
+    const SegStat st = load(sg);
+    if (st.m != -INFINITY) z += st.z * exp2(static_cast<double>(st.m - m) * static_cast<double>(c));
+  }
+#pragma unroll
+  for (int d = 8; d > 0; d >>= 1) z += __shfl_xor(z, d, 16);
+  m_out = m;
+  z_out = z;
+}
+
+// r(x)/q(x) of a drafted token x at residual level 0 from its two logits and the merged row statistics
+// (q: a logit, or the probability itself).  q(x) = 0 < p(x) accepts, q(x) = p(x) = 0 rejects.
+__device__ __forceinline__ double accept_ratio(double lp, float t_m, double t_invz, double lq, float q_m, double q_invz,
+                                               float c, bool q_is_probs) {
+  const double px = exp2((lp - static_cast<double>(t_m)) * static_cast<double>(c)) * t_invz;
+  const double qx = q_is_probs ? lq : exp2((lq - static_cast<double>(q_m)) * static_cast<double>(c)) * q_invz;
+  if (qx > 0.0) return px / qx;
+  return (px > 0.0) ? INFINITY : 0.0;
+}
+
+// ----------------------------------------------------------------------------------
+// Statistics pass for large batches of linear drafts that stops reading a request's rows once its chain is known
+// to have ended (Section 2.1: a rejection discards every later token).  Grid (segment, request, level), levels in
+// the order the chain needs them: target row 0, then for node j = 0, 1, ... its draft row and target row j + 1.
+// The 2 x nseg workgroups that produce the two rows of node j count their arrivals; the last one merges the two
+// rows' statistics, gathers the node's two logits and takes the accept decision with the arithmetic the
+// linear-draft kernel will use (same functions, same order: same bits); a rejection lowers stop[request] to j.
+// A workgroup of a later level looks at stop[request] first and returns without reading when its row lies
+// behind the stop.  Workgroups start roughly in grid order, so deep levels usually see the decisions of
+// shallow ones; nothing depends on it - whatever was skipped lies behind the final stop, and the linear-draft
+// kernel never uses a row behind its own first rejection, which is that same stop.
+// ----------------------------------------------------------------------------------
+constexpr int kProgMaxNodes = 64;
+constexpr int kProgStopStride = 32;        // ints between two requests' stop words: one 128-byte line each (every workgroup of a request reads its word)
+
+__global__ __launch_bounds__(kStatThreads) void accept_prog_init_kernel(unsigned* __restrict__ node_cnt, int n_cnt,
+                                                                       int* __restrict__ stop, unsigned* __restrict__ arrived, int B) {
+  for (int i = threadIdx.x; i < n_cnt; i += kStatThreads) node_cnt[i] = 0u;
+  for (int i = threadIdx.x; i < B; i += kStatThreads) { stop[i * kProgStopStride] = 0x7fffffff; arrived[i] = 0u; }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kStatThreads) void row_stats_prog_kernel(
+    const void* __restrict__ t_base, int t_dtype, int n_t_rows, const void* __restrict__ q_base, int q_dtype, int n_q_rows,
+    int V, float c, int nseg, SegStat* __restrict__ stats, const int32_t* __restrict__ node_offsets,
+    const int32_t* __restrict__ q_row, const int32_t* __restrict__ draft_tokens, const float* __restrict__ u_accept,
+    unsigned* __restrict__ node_cnt, int* __restrict__ stop) {
+  const int seg = blockIdx.x, b = blockIdx.y, k = blockIdx.z;
+  const int tid = threadIdx.x;
+  // (the three loads are independent: one round trip)
+  const int st = ld_dev(stop + b * kProgStopStride);
+  const int o = node_offsets[b];
+  int n = node_offsets[b + 1] - o;
+  n = n < 0 ? 0 : (n > kProgMaxNodes ? kProgMaxNodes : n);
+  const bool is_q = (k & 1) != 0;
+  const int j = is_q ? (k - 1) / 2 : k / 2 - 1;          // draft row of node j / target row j + 1 (k = 0: target row 0)
+  if (k > 0 && j >= n) return;                           // the request has no such row
+  if (k > 0 && (is_q ? st < j : st <= j)) return;        // the chain ended before this row is needed
+  const int64_t trow0 = static_cast<int64_t>(o) + b;
+  const void* base;
+  int dtype;
+  int64_t r, srow;
+  if (is_q) {
+    const int qr = min(max(q_row[o + j], 0), n_q_rows - 1);
+    base = q_base; dtype = q_dtype; r = qr; srow = static_cast<int64_t>(n_t_rows) + qr;
+  } else {
+    base = t_base; dtype = t_dtype; r = trow0 + j + 1; srow = r;
+  }
+  float M;
+  double Z;
+  const bool writer = segment_stats<VEC>(base, dtype, r * static_cast<int64_t>(V), seg * kStatSeg, V, c, M, Z);
+  // the node whose decision this row feeds: its own (draft row j) or the one tested against it (target row i: node i)
+  const int node = is_q ? j : j + 1;
+  if (tid >= kWave) return;           // what is left is one wave's work: the other waves free their slots now
+  const int lane = tid;
+  int last = 0;
+  if (writer) {                       // lane 0
+    unsigned long long* w = reinterpret_cast<unsigned long long*>(stats + srow * nseg + seg);
+    st_dev(w, static_cast<unsigned long long>(__float_as_uint(M)));
+    st_dev(w + 1, __builtin_bit_cast(unsigned long long, Z));
+    if (node < n) {
+      wait_stores();
+      const unsigned old = __hip_atomic_fetch_add(&node_cnt[b * kProgMaxNodes + node], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      last = (old == static_cast<unsigned>(2 * nseg - 1));
+    }
+  }
+  last = __shfl(last, 0, kWave);
+  if (!last) return;
+  // ---- both rows of `node` are complete: its accept decision, by this wave ----
+  const int x = min(max(draft_tokens[o + node], 0), V - 1);
+  const int qr = min(max(q_row[o + node], 0), n_q_rows - 1);
+  float m = 0.f;
+  double z = 1.0;
+  {
+    const int which = (lane >> 4) & 1, sl = lane & 15;   // lanes 0-15: the target row, 16-31: the draft row (32-63 repeat them)
+    const int64_t sr = which ? static_cast<int64_t>(n_t_rows) + qr : trow0 + node;
+    merged_row_stats<true>(stats + sr * nseg, nseg, c, sl, m, z);
+  }
+  const float m_t = __shfl(m, 0, kWave), m_q = __shfl(m, 16, kWave);
+  const double z_t = __shfl(z, 0, kWave), z_q = __shfl(z, 16, kWave);
+  if (lane == 0) {
+    const double lp = static_cast<double>(load_logit(t_base, t_dtype, (trow0 + node) * static_cast<int64_t>(V) + x));
+    const double lq = static_cast<double>(load_logit(q_base, q_dtype, static_cast<int64_t>(qr) * V + x));
+    const double ratio = accept_ratio(lp, m_t, 1.0 / z_t, lq, m_q, 1.0 / z_q, c, false);
+    if (!(static_cast<double>(u_accept[o + node]) < ratio))
+      __hip_atomic_fetch_min(stop + b * kProgStopStride, node, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 
 constexpr int kMaxHelpers = 3;
 
@@ -755,17 +900,9 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
     const int sl = tid & 15;
     for (int ri = tid >> 4; ri < n_rows; ri += (kLinThreads - kWave) / 16) {
       const int64_t srow = (ri <= n) ? trow0 + ri : static_cast<int64_t>(P.n_t_rows) + sh_qrow[ri - n - 1];
-      float m = -INFINITY;
-      for (int sg = sl; sg < P.nseg; sg += 16) m = fmaxf(m, P.stats[srow * P.nseg + sg].m);
-#pragma unroll
-      for (int d = 8; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 16));
-      double z = 0.0;
-      for (int sg = sl; sg < P.nseg; sg += 16) {
-        const SegStat st = P.stats[srow * P.nseg + sg];
-        if (st.m != -INFINITY) z += st.z * exp2(static_cast<double>(st.m - m) * static_cast<double>(c));
-      }
-#pragma unroll
-      for (int d = 8; d > 0; d >>= 1) z += __shfl_xor(z, d, 16);
+      float m;
+      double z;
+      merged_row_stats<false>(P.stats + srow * P.nseg, P.nseg, c, sl, m, z);
       if (sl == 0) {
         if (ri <= n) { sh_tm[ri] = m; sh_tinvz[ri] = 1.0 / z; }
         else { sh_qm[ri - n - 1] = m; sh_qinvz[ri - n - 1] = 1.0 / z; }
@@ -776,15 +913,9 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
   // (3) p(x_j), q(x_j) of every node in parallel (node j is tested against target row j, the distribution
   // after nodes 0..j-1), then the chain itself on LDS data
   __shared__ double sh_ratio[kMaxNodes];
-  if (tid < n) {
-    const double px = exp2((sh_px[tid] - static_cast<double>(sh_tm[tid])) * static_cast<double>(c)) * sh_tinvz[tid];
-    const double qx = q_is_probs ? sh_qx[tid]
-                                 : exp2((sh_qx[tid] - static_cast<double>(sh_qm[tid])) * static_cast<double>(c)) * sh_qinvz[tid];
-    double ratio;
-    if (qx > 0.0) ratio = px / qx;
-    else ratio = (px > 0.0) ? INFINITY : 0.0;
-    sh_ratio[tid] = ratio;
-  }
+  if (tid < n)
+    sh_ratio[tid] = accept_ratio(sh_px[tid], sh_tm[tid], sh_tinvz[tid], sh_qx[tid], q_is_probs ? 0.f : sh_qm[tid],
+                                 q_is_probs ? 0.0 : sh_qinvz[tid], c, q_is_probs);
   __syncthreads();
   int depth = 0, rejected = -1;
   for (int j = 0; j < n; ++j) {
@@ -980,7 +1111,7 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
 // Workspace: [row statistics][helper protocol: pass descriptors, hand-back slots (zeroed by the
 // statistics kernel)]
 struct AcceptLayout {
-  size_t words_off, n_zero_words, desc_off, part_off, arrived_off, msg_off, lin_off, total;
+  size_t words_off, n_zero_words, desc_off, part_off, arrived_off, msg_off, lin_off, prog_cnt_off, prog_stop_off, total;
 };
 
 static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
@@ -994,7 +1125,9 @@ static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
   l.msg_off = l.arrived_off + up(static_cast<size_t>(B) * sizeof(unsigned));   // arrival counters of the linear-draft kernel
   l.n_zero_words = (l.msg_off - l.words_off) / sizeof(unsigned);         // flags, descriptors, hand-back slots, counters
   l.lin_off = l.msg_off + up(cluster_msg_bytes(B));                      // messages of the cluster path
-  l.total = l.lin_off + up(static_cast<size_t>(B) * linear_units(V) * sizeof(double)) + 256;   // block sums of the linear-draft kernel
+  l.prog_cnt_off = l.lin_off + up(static_cast<size_t>(B) * linear_units(V) * sizeof(double));   // block sums of the linear-draft kernel
+  l.prog_stop_off = l.prog_cnt_off + up(static_cast<size_t>(B) * kProgMaxNodes * sizeof(unsigned));   // arrivals per node
+  l.total = l.prog_stop_off + up(static_cast<size_t>(B) * kProgStopStride * sizeof(int)) + 256;      // first rejection per request
   return l;
 }
 
@@ -1012,7 +1145,17 @@ static bool cluster_pays(int B, int V, int n_cu) {
 
 // Linear drafts take the statistics pass and accept_linear_kernel unless the caller asks for another path.
 static bool linear_path(const AcceptArgs& a) {
-  return a.parent == nullptr && (a.path == 0 || a.path == 3) && linear_units(a.V) <= kLinMaxUnits;
+  return a.parent == nullptr && (a.path == 0 || a.path == 3 || a.path == 4) && linear_units(a.V) <= kLinMaxUnits;
+}
+
+// The statistics pass that stops at each request's first rejection pays when the launch is several times what
+// the chip holds at once (about 2048 workgroups): later levels then start after the decisions of earlier ones.
+// It needs draft logits (their statistics are part of the decision) and computes the target rows itself.
+static bool progressive_stats(const AcceptArgs& a) {
+  if (!linear_path(a) || a.q_kind != 0 || a.target_stats_ready || a.total_nodes <= 0) return false;
+  if (a.max_nodes > kProgMaxNodes || a.B > 65535) return false;
+  const int64_t wgs = (static_cast<int64_t>(a.total_nodes) * 2 + a.B) * stats_segments(a.V);
+  return a.path == 4 || (a.path == 0 && wgs >= 6144);
 }
 
 const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
@@ -1020,6 +1163,7 @@ const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
   const bool cluster_ok = vec && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
                           a.q_kind == 0 && !a.target_stats_ready;
   const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && a.parent != nullptr && cluster_pays(a.B, a.V, n_cu)));
+  if (!cluster && progressive_stats(a)) return "row_stats_prog_kernel (rows up to each request's first rejection) + accept_linear_kernel (linear drafts: one vocabulary unit per workgroup, the last to arrive draws)";
   if (!cluster && linear_path(a)) return "row_stats_kernel (all rows) + accept_linear_kernel (linear drafts: one vocabulary unit per workgroup, the last to arrive draws)";
   if (!cluster) return "row_stats_kernel (all rows) + accept_walk_kernel (one workgroup per request, helper workgroups)";
   const ClusterPlan p = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
@@ -1048,7 +1192,24 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   }
   SegStat* stats = reinterpret_cast<SegStat*>(ws);
   unsigned* words = reinterpret_cast<unsigned*>(ws + lay.words_off);      // start of the zeroed region
-  if (!a.target_stats_ready) {
+  if (progressive_stats(a)) {
+    unsigned* node_cnt = reinterpret_cast<unsigned*>(ws + lay.prog_cnt_off);
+    int* stop = reinterpret_cast<int*>(ws + lay.prog_stop_off);
+    unsigned* arrived0 = reinterpret_cast<unsigned*>(ws + lay.arrived_off);
+    hipLaunchKernelGGL(accept_prog_init_kernel, dim3(1), dim3(kStatThreads), 0, stream, node_cnt, a.B * kProgMaxNodes, stop,
+                       arrived0, a.B);
+    const int nseg = stats_segments(a.V);
+    const dim3 grid_p(nseg, a.B, 2 * a.max_nodes + 1);
+    const bool vec_p = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
+    if (vec_p)
+      hipLaunchKernelGGL(row_stats_prog_kernel<true>, grid_p, dim3(kStatThreads), 0, stream, a.target, a.t_dtype, n_t_rows,
+                         a.draft_q, a.q_dtype, a.n_q_rows, a.V, c, nseg, stats, a.node_offsets, a.q_row, a.draft_tokens,
+                         a.u_accept, node_cnt, stop);
+    else
+      hipLaunchKernelGGL(row_stats_prog_kernel<false>, grid_p, dim3(kStatThreads), 0, stream, a.target, a.t_dtype, n_t_rows,
+                         a.draft_q, a.q_dtype, a.n_q_rows, a.V, c, nseg, stats, a.node_offsets, a.q_row, a.draft_tokens,
+                         a.u_accept, node_cnt, stop);
+  } else if (!a.target_stats_ready) {
     // rows nobody was drawn from exist only when there are more draft rows than nodes
     const bool sparse_q = n_q_stat_rows > a.total_nodes;
     launch_row_stats(a.target, a.t_dtype, n_t_rows, a.draft_q, a.q_dtype, n_q_stat_rows, a.V, c, stats, stream, words,

@@ -173,7 +173,7 @@ static int32_t accept_entry(bool prestats, const spec_accept_tuning* tuning, int
   a.max_nodes = max_nodes_per_req;
   a.path = 0; a.levels = 0; a.slices = 0; a.patience = -1; a.helpers = -1;
   if (tuning) {
-    if (tuning->path < 0 || tuning->path > 3 || tuning->levels < 0 || tuning->slices < 0) return SPEC_ERR_SHAPE;
+    if (tuning->path < 0 || tuning->path > 4 || tuning->levels < 0 || tuning->slices < 0) return SPEC_ERR_SHAPE;
     a.path = tuning->path; a.levels = tuning->levels; a.slices = tuning->slices;
     a.patience = tuning->patience; a.helpers = tuning->helpers;
   }

@@ -36,7 +36,8 @@ struct AcceptArgs {
   void* workspace;
   bool target_stats_ready;     // the workspace already starts with the target rows' statistics
   // per-call tuning (spec_accept_tuned); zero / negative = the library's choice
-  int path;                    // 0: library's choice, 1: statistics kernel + one-workgroup walk, 2: workgroup clusters
+  int path;                    // 0: library's choice, 1: statistics kernel + one-workgroup walk, 2: workgroup clusters,
+                               // 3 / 4: linear-draft kernel after the statistics of all rows / of the rows up to each first rejection
   int levels, slices;          // cluster path: window levels, vocabulary slices per level
   int patience;                // polls spent waiting for peer workgroups (< 0: default)
   int helpers;                 // statistics + walk path: helper workgroups per request (< 0: default)

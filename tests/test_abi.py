@@ -147,7 +147,7 @@ def test_tuned_accept_and_plan_descriptions_need_no_gpu():
                                    null, 0, null, 0, 0, null, 1.0, null, null, null, null, 3, null, null, null, 0, null)
 
     assert tuned(None) == -1                                    # like spec_accept: NULL tensors
-    assert tuned(sv.SpecAcceptTuning(path=4)) == -1             # tensors are checked first ...
+    assert tuned(sv.SpecAcceptTuning(path=5)) == -1             # tensors are checked first ...
     assert tuned(sv.SpecAcceptTuning(path=2), B=0) == 0         # ... and an empty batch is nothing to do
     desc = sv.make_attn_desc(batch=16, num_q_heads=32, num_kv_heads=8, head_dim=128, total_q=1024,
                              max_q_per_req=64, max_pages_per_req=260, total_kv_tokens_hint=16 * 4160)

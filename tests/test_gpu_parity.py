@@ -219,6 +219,36 @@ def test_accept_linear_kernel_matches_oracle(rt, name):
     assert np.array_equal(got["stop_node"], walk["stop_node"]) or ties > 0
 
 
+@pytest.mark.parametrize("name", list(LINEAR_CASES))
+def test_accept_statistics_that_stop_at_the_first_rejection(rt, name):
+    """Path 4: the statistics pass skips rows behind each request's first rejection (it takes the accept decisions
+    itself, with the arithmetic of the linear-draft kernel).  Rows it skips hold whatever the workspace held before
+    - the workspace is filled with NaN patterns and with huge values here - and the results must be those of path 3
+    bit for bit, and the oracle's outside near-ties."""
+    cfg, opt = LINEAR_CASES[name]
+    ai = W.make_accept_inputs(cfg, seed=9)
+    fp32 = opt.get("fp32", False)
+    tl, dq = ai.target_logits, ai.draft_q
+    if fp32:
+        tl, dq = W.bf16_bits_to_f32(tl), W.bf16_bits_to_f32(dq)
+    ref = oracle.accept(ai.st.node_offsets, ai.st.parent, ai.draft_tokens, tl, dq, ai.q_row, ai.u_accept,
+                        ai.u_resample, temperature=cfg.temperature)
+    outs = {}
+    for path, fill in ((3, 0), (4, 0xFF), (4, 0x7B)):
+        dev = rt.DeviceAccept(ai.st, tl, dq, ai.q_row, ai.draft_tokens, ai.u_accept, ai.u_resample,
+                              temperature=cfg.temperature)
+        dev.workspace.fill_(fill)
+        dev.run(tuning=_tuning(path=path))
+        outs[(path, fill)] = dev.results()
+    base = outs[(3, 0)]
+    bad, ties, B = compare_accept(base, ref, ai.st.n)
+    assert not bad and ties <= max(1, B // 4)
+    for key, got in outs.items():
+        for f in ("accept_len", "out_tokens", "stop_node"):
+            assert np.array_equal(got[f], base[f]), (key, f)
+        assert np.array_equal(got["ratio"], base["ratio"], equal_nan=True), key
+
+
 def test_accept_linear_kernel_probability_drafts(rt):
     """Draft rows given as probabilities (SPEC_Q_PROBS) through the linear-draft kernel."""
     cfg = W.scaled(C["c1_llama2_7b"], batch=6, vocab=6000)
