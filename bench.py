@@ -384,9 +384,11 @@ def measure(name, args, cpu_seconds):
     if args.accept_mode == "greedy":
         accept_plan = "row_argmax_kernel + greedy_walk_kernel"
     elif lm is not None:
-        accept_plan = "row_stats_kernel (draft rows only) + accept_walk_kernel, target statistics from spec_lm_head"
+        accept_plan = ("row_stats_kernel (draft rows only) + " +
+                       ("accept_linear_kernel" if a.st.parent is None else "accept_walk_kernel") +
+                       ", target statistics from spec_lm_head")
     else:
-        accept_plan = sv.spec_describe_accept_plan(cfg.batch, cfg.vocab, int(a.st.n.max()), a.st.parent is not None,
+        accept_plan = sv.spec_describe_accept_plan(cfg.batch, cfg.vocab, int(a.st.total), int(a.st.n.max()), a.st.parent is not None,
                                                    q_kind=c0.accept.q_kind, q_dtype=sv._dtype_code(c0.accept.draft_q),
                                                    tuning=c0.tuning)
     step_s = elapsed / args.steps

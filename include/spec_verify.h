@@ -233,8 +233,8 @@ int32_t spec_accept_noalloc(
     int32_t* stop_node, float* dbg_ratio, void* stream);
 
 /* One-line description of what spec_accept launches for this shape on the current device
- * (host; for logs and benchmark reports). */
-int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V,
+ * (host; for logs and benchmark reports).  total_nodes as for spec_accept. */
+int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t total_nodes,
                                   int32_t max_nodes_per_req, int32_t is_tree, int32_t target_dtype,
                                   int32_t q_dtype, int32_t q_kind, char* buf, size_t buf_bytes);
 

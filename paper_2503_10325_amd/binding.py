@@ -103,7 +103,7 @@ def lib() -> ctypes.CDLL:
         L.spec_describe_attn_plan.restype = i32
         L.spec_describe_attn_plan.argtypes = [ctypes.POINTER(SpecAttnDesc), ctypes.c_char_p, sz]
         L.spec_describe_accept_plan.restype = i32
-        L.spec_describe_accept_plan.argtypes = [ctypes.POINTER(SpecAcceptTuning)] + [i32] * 7 + [ctypes.c_char_p, sz]
+        L.spec_describe_accept_plan.argtypes = [ctypes.POINTER(SpecAcceptTuning)] + [i32] * 8 + [ctypes.c_char_p, sz]
         L.spec_row_stats_size.restype = sz
         L.spec_row_stats_size.argtypes = [i32, i32]
         L.spec_lm_head_workspace_size.restype = sz
@@ -248,11 +248,11 @@ def spec_describe_attn_plan(desc: SpecAttnDesc) -> str:
     return buf.value.decode()
 
 
-def spec_describe_accept_plan(B, V, max_nodes_per_req, is_tree, target_dtype=SPEC_BF16, q_dtype=SPEC_BF16,
+def spec_describe_accept_plan(B, V, total_nodes, max_nodes_per_req, is_tree, target_dtype=SPEC_BF16, q_dtype=SPEC_BF16,
                               q_kind=SPEC_Q_LOGITS, tuning=None) -> str:
     buf = ctypes.create_string_buffer(512)
-    rc = lib().spec_describe_accept_plan(None if tuning is None else ctypes.byref(tuning), B, V, max_nodes_per_req,
-                                         int(bool(is_tree)), target_dtype, q_dtype, q_kind, buf, 512)
+    rc = lib().spec_describe_accept_plan(None if tuning is None else ctypes.byref(tuning), B, V, total_nodes,
+                                         max_nodes_per_req, int(bool(is_tree)), target_dtype, q_dtype, q_kind, buf, 512)
     if rc != SPEC_OK:
         raise SpecError("spec_describe_accept_plan", rc)
     return buf.value.decode()

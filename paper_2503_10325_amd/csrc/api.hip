@@ -38,7 +38,7 @@ const char* spec_strerror(int32_t status) {
   }
 }
 
-int32_t spec_abi_version(void) { return 2; }
+int32_t spec_abi_version(void) { return 3; }
 
 static int check_attn_desc(const spec_attn_desc* d) {
   if (!d) return SPEC_ERR_NULL;
@@ -225,13 +225,14 @@ int32_t spec_accept_noalloc(int32_t B, int32_t V, int32_t total_nodes, int32_t n
                       kNoallocScratchBytes, stream);
 }
 
-int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t max_nodes_per_req,
-                                  int32_t is_tree, int32_t target_dtype, int32_t q_dtype, int32_t q_kind,
-                                  char* buf, size_t buf_bytes) {
-  if (B < 0 || V <= 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
+int32_t spec_describe_accept_plan(const spec_accept_tuning* tuning, int32_t B, int32_t V, int32_t total_nodes,
+                                  int32_t max_nodes_per_req, int32_t is_tree, int32_t target_dtype, int32_t q_dtype,
+                                  int32_t q_kind, char* buf, size_t buf_bytes) {
+  if (B < 0 || V <= 0 || max_nodes_per_req < 0 || total_nodes < 0) return SPEC_ERR_SHAPE;
   if (!buf || buf_bytes == 0) return SPEC_ERR_NULL;
   AcceptArgs a{};
-  a.B = B; a.V = V; a.max_nodes = max_nodes_per_req; a.t_dtype = target_dtype; a.q_dtype = q_dtype; a.q_kind = q_kind;
+  a.B = B; a.V = V; a.total_nodes = total_nodes; a.max_nodes = max_nodes_per_req;
+  a.t_dtype = target_dtype; a.q_dtype = q_dtype; a.q_kind = q_kind;
   static const int32_t some_parent = 0;
   a.parent = is_tree ? &some_parent : nullptr;       // only its being NULL or not matters to the plan
   a.patience = -1; a.helpers = -1;

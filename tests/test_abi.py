@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(sv.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
-    assert sv.lib().spec_abi_version() == 2
+    assert sv.lib().spec_abi_version() == 3
     assert sv.strerror(0) == "ok" and "workspace" in sv.strerror(-4)
 
 
@@ -153,9 +153,13 @@ def test_tuned_accept_and_plan_descriptions_need_no_gpu():
                              max_q_per_req=64, max_pages_per_req=260, total_kv_tokens_hint=16 * 4160)
     text = sv.spec_describe_attn_plan(desc)
     assert "attn_" in text and "chunks" in text
-    text = sv.spec_describe_accept_plan(16, 128256, 64, True)
+    text = sv.spec_describe_accept_plan(16, 128256, 1024, 64, True)
     assert "accept_cluster_kernel" in text
-    text = sv.spec_describe_accept_plan(16, 128256, 64, True, target_dtype=sv.SPEC_F32)
+    text = sv.spec_describe_accept_plan(16, 128256, 1024, 64, True, target_dtype=sv.SPEC_F32)
     assert "row_stats_kernel" in text
-    text = sv.spec_describe_accept_plan(16, 128256, 64, True, tuning=sv.SpecAcceptTuning(path=1))
+    text = sv.spec_describe_accept_plan(16, 128256, 1024, 64, True, tuning=sv.SpecAcceptTuning(path=1))
     assert "row_stats_kernel" in text
+    text = sv.spec_describe_accept_plan(8, 32000, 64, 8, False)                 # a small batch of linear drafts
+    assert "row_stats_kernel" in text and "accept_linear_kernel" in text
+    text = sv.spec_describe_accept_plan(64, 128256, 365, 10, False)             # a large one
+    assert "row_stats_prog_kernel" in text and "accept_linear_kernel" in text

@@ -388,13 +388,14 @@ def test_accept_with_probability_rows(rt):
     assert not bad
 
 
-def test_accept_zero_nodes_request(rt):
+@pytest.mark.parametrize("path", [0, 1, 3, 4])
+def test_accept_zero_nodes_request(rt, path):
     cfg = W.scaled(C["c1_llama2_7b"], batch=4, vocab=1000, draft=("linear", 3))
     st = W.make_structure(cfg, seed=2)
     st.n[2] = 0
     st.node_offsets[1:] = np.cumsum(st.n)
     ai = W.make_accept_inputs(cfg, seed=2, st=st)
-    got, ref = _run_accept(rt, cfg, ai)
+    got, ref = _run_accept(rt, cfg, ai, tuning=_tuning(path=path) if path else None)
     bad, ties, _ = compare_accept(got, ref, st.n)
     assert not bad and got["accept_len"][2] == 0
 
