@@ -316,12 +316,14 @@ __device__ __forceinline__ double accept_ratio(double lp, float t_m, double t_in
 // kernel never uses a row behind its own first rejection, which is that same stop.
 // ----------------------------------------------------------------------------------
 constexpr int kProgMaxNodes = 64;
+constexpr int kCntStride = 32;             // ints between two arrival counters: one 128-byte line each
 constexpr int kProgStopStride = 32;        // ints between two requests' stop words: one 128-byte line each (every workgroup of a request reads its word)
 
 __global__ __launch_bounds__(kStatThreads) void accept_prog_init_kernel(unsigned* __restrict__ node_cnt, int n_cnt,
                                                                        int* __restrict__ stop, unsigned* __restrict__ arrived, int B) {
-  for (int i = threadIdx.x; i < n_cnt; i += kStatThreads) node_cnt[i] = 0u;
-  for (int i = threadIdx.x; i < B; i += kStatThreads) { stop[i * kProgStopStride] = 0x7fffffff; arrived[i] = 0u; }
+  const int t = blockIdx.x * kStatThreads + threadIdx.x, nt = gridDim.x * kStatThreads;
+  for (int i = t; i < n_cnt; i += nt) node_cnt[i * kCntStride] = 0u;
+  for (int i = t; i < B; i += nt) { stop[i * kProgStopStride] = 0x7fffffff; arrived[i * kCntStride] = 0u; }
 }
 
 template <bool VEC>
@@ -329,14 +331,14 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_prog_kernel(
     const void* __restrict__ t_base, int t_dtype, int n_t_rows, const void* __restrict__ q_base, int q_dtype, int n_q_rows,
     int V, float c, int nseg, SegStat* __restrict__ stats, const int32_t* __restrict__ node_offsets,
     const int32_t* __restrict__ q_row, const int32_t* __restrict__ draft_tokens, const float* __restrict__ u_accept,
-    unsigned* __restrict__ node_cnt, int* __restrict__ stop) {
+    unsigned* __restrict__ node_cnt, int* __restrict__ stop, int max_nodes) {
   const int seg = blockIdx.x, b = blockIdx.y, k = blockIdx.z;
   const int tid = threadIdx.x;
   // (the three loads are independent: one round trip)
   const int st = ld_dev(stop + b * kProgStopStride);
   const int o = node_offsets[b];
   int n = node_offsets[b + 1] - o;
-  n = n < 0 ? 0 : (n > kProgMaxNodes ? kProgMaxNodes : n);
+  n = n < 0 ? 0 : (n > max_nodes ? max_nodes : n);
   const bool is_q = (k & 1) != 0;
   const int j = is_q ? (k - 1) / 2 : k / 2 - 1;          // draft row of node j / target row j + 1 (k = 0: target row 0)
   if (k > 0 && j >= n) return;                           // the request has no such row
@@ -365,7 +367,7 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_prog_kernel(
     st_dev(w + 1, __builtin_bit_cast(unsigned long long, Z));
     if (node < n) {
       wait_stores();
-      const unsigned old = __hip_atomic_fetch_add(&node_cnt[b * kProgMaxNodes + node], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned old = __hip_atomic_fetch_add(&node_cnt[static_cast<int64_t>(o + node) * kCntStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       last = (old == static_cast<unsigned>(2 * nseg - 1));
     }
   }
@@ -1003,7 +1005,7 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
       if (i < bpu && unit * bpu + i < nblocks) st_dev(&partial[static_cast<int64_t>(b) * nblocks + unit * bpu + i], tot[i]);
     wait_stores();
     unsigned old = 0;
-    if (lane == 0) old = __hip_atomic_fetch_add(&arrived[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) old = __hip_atomic_fetch_add(&arrived[b * kCntStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     sh_last = (old == static_cast<unsigned>(U - 1));
   }
@@ -1122,11 +1124,11 @@ static AcceptLayout accept_layout(int B, int total_nodes, int n_q_rows, int V) {
   l.desc_off = l.words_off;
   l.part_off = l.desc_off + up(static_cast<size_t>(B) * sizeof(PassDesc));
   l.arrived_off = l.part_off + up(static_cast<size_t>(B) * kMaxHelpers * kWalkWaves * sizeof(PartSlot));
-  l.msg_off = l.arrived_off + up(static_cast<size_t>(B) * sizeof(unsigned));   // arrival counters of the linear-draft kernel
+  l.msg_off = l.arrived_off + up(static_cast<size_t>(B) * kCntStride * sizeof(unsigned));   // arrival counters of the linear-draft kernel
   l.n_zero_words = (l.msg_off - l.words_off) / sizeof(unsigned);         // flags, descriptors, hand-back slots, counters
   l.lin_off = l.msg_off + up(cluster_msg_bytes(B));                      // messages of the cluster path
   l.prog_cnt_off = l.lin_off + up(static_cast<size_t>(B) * linear_units(V) * sizeof(double));   // block sums of the linear-draft kernel
-  l.prog_stop_off = l.prog_cnt_off + up(static_cast<size_t>(B) * kProgMaxNodes * sizeof(unsigned));   // arrivals per node
+  l.prog_stop_off = l.prog_cnt_off + up(static_cast<size_t>(total_nodes) * kCntStride * sizeof(unsigned));   // arrivals per node
   l.total = l.prog_stop_off + up(static_cast<size_t>(B) * kProgStopStride * sizeof(int)) + 256;      // first rejection per request
   return l;
 }
@@ -1196,19 +1198,20 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
     unsigned* node_cnt = reinterpret_cast<unsigned*>(ws + lay.prog_cnt_off);
     int* stop = reinterpret_cast<int*>(ws + lay.prog_stop_off);
     unsigned* arrived0 = reinterpret_cast<unsigned*>(ws + lay.arrived_off);
-    hipLaunchKernelGGL(accept_prog_init_kernel, dim3(1), dim3(kStatThreads), 0, stream, node_cnt, a.B * kProgMaxNodes, stop,
-                       arrived0, a.B);
+    const int n_cnt = a.total_nodes;
+    hipLaunchKernelGGL(accept_prog_init_kernel, dim3((n_cnt + kStatThreads - 1) / kStatThreads), dim3(kStatThreads), 0, stream,
+                       node_cnt, n_cnt, stop, arrived0, a.B);
     const int nseg = stats_segments(a.V);
     const dim3 grid_p(nseg, a.B, 2 * a.max_nodes + 1);
     const bool vec_p = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
     if (vec_p)
       hipLaunchKernelGGL(row_stats_prog_kernel<true>, grid_p, dim3(kStatThreads), 0, stream, a.target, a.t_dtype, n_t_rows,
                          a.draft_q, a.q_dtype, a.n_q_rows, a.V, c, nseg, stats, a.node_offsets, a.q_row, a.draft_tokens,
-                         a.u_accept, node_cnt, stop);
+                         a.u_accept, node_cnt, stop, a.max_nodes);
     else
       hipLaunchKernelGGL(row_stats_prog_kernel<false>, grid_p, dim3(kStatThreads), 0, stream, a.target, a.t_dtype, n_t_rows,
                          a.draft_q, a.q_dtype, a.n_q_rows, a.V, c, nseg, stats, a.node_offsets, a.q_row, a.draft_tokens,
-                         a.u_accept, node_cnt, stop);
+                         a.u_accept, node_cnt, stop, a.max_nodes);
   } else if (!a.target_stats_ready) {
     // rows nobody was drawn from exist only when there are more draft rows than nodes
     const bool sparse_q = n_q_stat_rows > a.total_nodes;
