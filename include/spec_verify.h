@@ -73,7 +73,8 @@ typedef struct {
   int32_t head_dim;          /* D: 64 or 128                                        */
   int32_t page_size;         /* tokens per cache page: 16                           */
   int32_t total_q;           /* sum_b n[b] = q_offsets[B]                           */
-  int32_t max_q_per_req;     /* upper bound of n[b]; at most 64                     */
+  int32_t max_q_per_req;     /* upper bound of n[b]; at most 128 (above 64: two
+                                ancestor-mask words per node, row-split kernels)    */
   int32_t max_pages_per_req; /* row stride of block_table; >= ceil((ctx+n)/page)    */
   int64_t total_kv_tokens_hint; /* host's estimate of sum_b (ctx_len[b]+n[b]); 0 = unknown.
                                    Only steers how the context is split into chunks. */
@@ -163,7 +164,7 @@ int32_t spec_accept(
     int32_t B, int32_t V,
     int32_t total_nodes,         /* = node_offsets[B] (host copy)                      */
     int32_t n_q_rows,            /* rows of draft_q                                    */
-    int32_t max_nodes_per_req,   /* upper bound of n[b]; at most 64                    */
+    int32_t max_nodes_per_req,   /* upper bound of n[b]; at most 128                   */
     const int32_t* node_offsets, /* [B+1]                                              */
     const int32_t* parent,       /* [total_nodes] or NULL = linear chain               */
     const int32_t* draft_tokens, /* [total_nodes] in [0, V)                            */
@@ -257,7 +258,7 @@ size_t spec_accept_greedy_workspace_size(int32_t B, int32_t total_nodes, int32_t
 int32_t spec_accept_greedy(
     int32_t B, int32_t V,
     int32_t total_nodes,         /* = node_offsets[B] (host copy)                      */
-    int32_t max_nodes_per_req,   /* upper bound of n[b]; at most 64                    */
+    int32_t max_nodes_per_req,   /* upper bound of n[b]; at most 128                   */
     const int32_t* node_offsets, /* [B+1]                                              */
     const int32_t* parent,       /* [total_nodes] or NULL = linear chain               */
     const int32_t* draft_tokens, /* [total_nodes]                                      */
@@ -332,7 +333,7 @@ int32_t spec_adaptive_speculation(
  * ctx_len[b] + d, in both pools, for every KV head.  Linear drafts need no move and are
  * left untouched.  Pools and block table as in spec_verify_attn; the pools are modified
  * in place.  new_len[b] = ctx_len[b] + path length.  head_dim 64 or 128, page_size 16,
- * at most 64 nodes per request.
+ * at most 128 nodes per request.
  * ---------------------------------------------------------------------------- */
 int32_t spec_compact_kv(
     int32_t B, int32_t num_kv_heads, int32_t head_dim, int32_t page_size, int32_t max_pages_per_req,

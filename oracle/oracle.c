@@ -496,12 +496,14 @@ int oracle_compact_kv(int B, int Hkv, int D, int page, int max_pages, uint16_t* 
                       const int32_t* parent, const int32_t* stop_node, int32_t* new_len) {
   for (int b = 0; b < B; ++b) {
     const int o = q_offsets[b], n = q_offsets[b + 1] - o;
-    int path[64], depth = 0;
-    for (int a = stop_node[b]; a >= 0 && a < n && depth < 64; a = parent ? parent[o + a] : a - 1) path[depth++] = a;
+    int* path = (int*)malloc(sizeof(int) * (size_t)(n > 0 ? n : 1));   /* a path has at most n nodes */
+    if (!path) return -7;
+    int depth = 0;
+    for (int a = stop_node[b]; a >= 0 && a < n && depth < n; a = parent ? parent[o + a] : a - 1) path[depth++] = a;
     /* path[] runs leaf -> root; position d from the root is path[depth - 1 - d] */
     const size_t row = (size_t)D;
     uint16_t* tmp = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)(depth > 0 ? depth : 1) * 2 * Hkv * row);
-    if (!tmp) return -7;
+    if (!tmp) { free(path); return -7; }
     for (int d = 0; d < depth; ++d) {
       const int pos = ctx_len[b] + path[depth - 1 - d];
       const int64_t pg = block_table[(int64_t)b * max_pages + pos / page];
@@ -521,6 +523,7 @@ int oracle_compact_kv(int B, int Hkv, int D, int page, int max_pages, uint16_t* 
       }
     }
     free(tmp);
+    free(path);
     if (new_len) new_len[b] = ctx_len[b] + depth;
   }
   return 0;

@@ -131,7 +131,7 @@ void launch_row_stats(const void* t_base, int t_dtype, int n_t_rows, const void*
 // ----------------------------------------------------------------------------------
 constexpr int kWalkThreads = 1024;
 constexpr int kWalkWaves = kWalkThreads / kWave;
-constexpr int kMaxNodes = 64;
+constexpr int kMaxNodes = 128;
 constexpr int kMaxBlocksPerSeg = 256;      // vocabularies up to 16 * 256 * 512 = 2M tokens
 
 struct WalkRows {
@@ -558,10 +558,10 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   // (2) in one round trip: the two logits of every drafted token (last wave) and the merged
   // statistics of the n+1 target rows and n draft rows (groups of 16 lanes, one segment each)
   if (wave == kWalkWaves - 1) {
-    if (lane < n) {
-      const int x = sh_tok[lane];
-      sh_px[lane] = static_cast<double>(load_logit(P.target, P.t_dtype, (trow0 + 1 + sh_par[lane]) * static_cast<int64_t>(V) + x));
-      sh_qx[lane] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, static_cast<int64_t>(sh_qrow[lane]) * V + x));
+    for (int j = lane; j < n; j += kWave) {
+      const int x = sh_tok[j];
+      sh_px[j] = static_cast<double>(load_logit(P.target, P.t_dtype, (trow0 + 1 + sh_par[j]) * static_cast<int64_t>(V) + x));
+      sh_qx[j] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, static_cast<int64_t>(sh_qrow[j]) * V + x));
     }
   } else {
     const int n_rows = (n + 1) + (q_is_probs ? 0 : n);
@@ -595,7 +595,9 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   }
   __syncthreads();
 
-  const int my_parent = (lane < n) ? sh_par[lane] : -2;   // lanes >= n hold an impossible parent
+  // lane l looks after nodes l and l + 64; nodes that do not exist hold an impossible parent
+  const int my_parent = (lane < n) ? sh_par[lane] : -2;
+  const int my_parent_hi = (lane + kWave < n) ? sh_par[lane + kWave] : -2;
 
   int cur = -1, depth = 0;
   WalkRows R;
@@ -680,11 +682,14 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
     sums_level = -1;
     R.have_q = 0;
 
+    // children of the current node in index order: two ballot words
     unsigned long long kids = __ballot(my_parent == cur && lane > cur);
+    unsigned long long kids_hi = __ballot(my_parent_hi == cur && lane + kWave > cur);
     int accepted = -1;
-    while (kids) {
-      const int ch = __ffsll(static_cast<long long>(kids)) - 1;
-      kids &= kids - 1;
+    while (kids | kids_hi) {
+      int ch;
+      if (kids) { ch = __ffsll(static_cast<long long>(kids)) - 1; kids &= kids - 1; }
+      else { ch = kWave + __ffsll(static_cast<long long>(kids_hi)) - 1; kids_hi &= kids_hi - 1; }
       if (!R.have_q) {
         R.q_off = static_cast<int64_t>(sh_qrow[ch]) * V;
         R.q_m = sh_qm[ch];
@@ -892,10 +897,10 @@ __global__ __launch_bounds__(kLinThreads, 2) void accept_linear_kernel(AcceptPar
   // (2) the two logits of every drafted token (last wave) and the merged statistics of the n+1 target rows and
   // the n draft rows (groups of 16 lanes, one segment each)
   if (wave == kLinWaves - 1) {
-    if (lane < n) {
-      const int x = sh_tok[lane];
-      sh_px[lane] = static_cast<double>(load_logit(P.target, P.t_dtype, (trow0 + lane) * static_cast<int64_t>(V) + x));
-      sh_qx[lane] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, static_cast<int64_t>(sh_qrow[lane]) * V + x));
+    for (int j = lane; j < n; j += kWave) {
+      const int x = sh_tok[j];
+      sh_px[j] = static_cast<double>(load_logit(P.target, P.t_dtype, (trow0 + j) * static_cast<int64_t>(V) + x));
+      sh_qx[j] = static_cast<double>(load_logit(P.draft_q, P.q_dtype, static_cast<int64_t>(sh_qrow[j]) * V + x));
     }
   } else {
     const int n_rows = (n + 1) + (q_is_probs ? 0 : n);

@@ -39,7 +39,7 @@ constexpr int kClThreads = 256;             // four waves, one per SIMD: the per
                                             // scalar steps cost a quarter of what sixteen waves would pay
 constexpr int kClWaves = kClThreads / kWave;
 constexpr int kClUnit = kClThreads * 8;        // logits one workgroup-wide 16-byte load covers (2048)
-constexpr int kClNodes = 64;
+constexpr int kClNodes = 128;
 constexpr int kClMaxUpt = 16;                  // units per slice: 16 x 4 KiB per row, two rows = 128 KiB of LDS
 constexpr int kClMaxParts = kClMaxUpt * kClWaves;
 constexpr unsigned kClAbort = 0xffffffffu;
@@ -227,7 +227,9 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
   __syncthreads();
   if (tid <= kClNodes && sh_fc[tid] >= kClNodes) sh_fc[tid] = -2;   // no child
   __syncthreads();
-  const int my_parent = (lane < n) ? sh_par[lane] : -3;   // lanes >= n hold an impossible parent
+  // lane l looks after nodes l and l + 64; nodes that do not exist hold an impossible parent
+  const int my_parent = (lane < n) ? sh_par[lane] : -3;
+  const int my_parent_hi = (lane + 64 < n) ? sh_par[lane + 64] : -3;
 
   // ---- the slice held in LDS ----
   auto row_p = [&](int u) -> u32x4* { return reinterpret_cast<u32x4*>(cl_rows) + (u * kClThreads + tid); };
@@ -487,10 +489,12 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
         };
 
         unsigned long long kids = __ballot(my_parent == cur && lane > cur);
+        unsigned long long kids_hi = __ballot(my_parent_hi == cur && lane + 64 > cur);
         int accepted = -1;
-        while (kids) {
-          const int ch = __ffsll(static_cast<long long>(kids)) - 1;
-          kids &= kids - 1;
+        while (kids | kids_hi) {
+          int ch;
+          if (kids) { ch = __ffsll(static_cast<long long>(kids)) - 1; kids &= kids - 1; }
+          else { ch = 64 + __ffsll(static_cast<long long>(kids_hi)) - 1; kids_hi &= kids_hi - 1; }
           const double qx = exp2((static_cast<double>(sh_lq[ch]) - static_cast<double>(S.mq)) * static_cast<double>(c)) * S.izq;
           double rx = exp2((static_cast<double>(sh_lp[ch]) - static_cast<double>(S.mp)) * static_cast<double>(c)) * S.izp;
           for (int k = 0; k < level; ++k) {

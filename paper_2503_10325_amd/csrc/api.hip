@@ -48,7 +48,7 @@ static int check_attn_desc(const spec_attn_desc* d) {
   if (d->num_q_heads % d->num_kv_heads != 0) return SPEC_ERR_SHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return SPEC_ERR_UNSUPPORTED;
   if (d->page_size != 16) return SPEC_ERR_UNSUPPORTED;
-  if (d->max_q_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (d->max_q_per_req > 128) return SPEC_ERR_UNSUPPORTED;
   if (d->out_dtype != SPEC_BF16 && d->out_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
   if (d->batch > 65535 || d->num_kv_heads > 65535) return SPEC_ERR_UNSUPPORTED;
   if (!(d->scale >= 0.f)) return SPEC_ERR_SHAPE;
@@ -150,7 +150,7 @@ static int32_t accept_entry(bool prestats, const spec_accept_tuning* tuning, int
                             float* dbg_ratio, void* workspace, size_t workspace_bytes, void* stream) {
   if (B < 0 || V <= 0 || total_nodes < 0 || n_q_rows < 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
   if (!(temperature > 0.f)) return SPEC_ERR_SHAPE;
-  if (max_nodes_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (max_nodes_per_req > 128) return SPEC_ERR_UNSUPPORTED;
   if (V > 2097152) return SPEC_ERR_UNSUPPORTED;        // the walk kernel indexes a row by 16 x 256 blocks of 512
   if (out_stride < max_nodes_per_req + 1) return SPEC_ERR_SHAPE;
   if ((target_dtype != SPEC_BF16 && target_dtype != SPEC_F32) || (q_dtype != SPEC_BF16 && q_dtype != SPEC_F32))
@@ -299,7 +299,7 @@ int32_t spec_accept_greedy(int32_t B, int32_t V, int32_t total_nodes, int32_t ma
                            int32_t* out_tokens, int32_t out_stride, int32_t* stop_node, int32_t* row_argmax,
                            void* workspace, size_t workspace_bytes, void* stream) {
   if (B < 0 || V <= 0 || total_nodes < 0 || max_nodes_per_req < 0) return SPEC_ERR_SHAPE;
-  if (max_nodes_per_req > 64) return SPEC_ERR_UNSUPPORTED;
+  if (max_nodes_per_req > 128) return SPEC_ERR_UNSUPPORTED;
   if (out_stride < max_nodes_per_req + 1) return SPEC_ERR_SHAPE;
   if (target_dtype != SPEC_BF16 && target_dtype != SPEC_F32) return SPEC_ERR_UNSUPPORTED;
   if (static_cast<int64_t>(total_nodes) + B > 65535) return SPEC_ERR_UNSUPPORTED;   // rows are the grid's y dimension

@@ -34,7 +34,8 @@ constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = 4;
 constexpr int kTile = 32;          // tokens per wave iteration
 constexpr int kPage = 16;
-constexpr int kMaxQ = 64;
+constexpr int kMaxQ = 64;             // query nodes per request with one ancestor-mask word
+constexpr int kMaxQWide = 128;        // ... with two (row-split kernels only)
 
 template <int D>
 struct AttnCfg {
@@ -69,7 +70,8 @@ struct AttnParams {
   int B, Hq, Hkv, G, max_pages, chunk_tokens, max_chunks;
   int tau;           // > 0: a request is cut so that one wave streams at most tau tiles per work item
   int list_rows_min; // > 0 (work list only): requests with this many query rows per KV head use the row-split body
-  int list_rows_units;  // eighths of a work-list unit that 32 tokens of such a request cost
+  int list_rows_units;
+  int n_cap;                  // query nodes per request the launched kernels handle (64, or 128 with two mask words)  // eighths of a work-list unit that 32 tokens of such a request cost
   float c;           // scale * log2(e)
   int out_f32;
 };
@@ -540,14 +542,18 @@ struct RowsCfg {
   static constexpr int kStage = kKBytes + kVBytes;
   static constexpr int kMaxChunkPages = NW == 8 ? 1024 : 512;   // a chunk spans at most 16384 (8192) tokens
   static constexpr int kPagePad = 32;                      // page-table entries kept past a chunk's last page
-  static constexpr int kLds = 2 * kStage + 768 + (kMaxChunkPages + kPagePad) * 4;
+  // behind the two stages: ancestor masks, parents, page table
+  static constexpr int meta_bytes(bool wide) { return wide ? kMaxQWide * 16 + kMaxQWide * 4 : kMaxQ * 8 + kMaxQ * 4; }
+  static constexpr int lds_bytes(bool wide) { return 2 * kStage + meta_bytes(wide) + (kMaxChunkPages + kPagePad) * 4; }
+  static constexpr int kLds = lds_bytes(false);
   static_assert(kTpt == 4 || kTpt == 2, "unsupported tile/thread combination");
 };
 
 // One work item of the row-split body: (request b, KV head kvh, context chunk `chunk` of `nchunks`, row group
 // rg).  The request's context is cut into nchunks pieces of cb tokens (a multiple of the tile).  Every return
 // below is workgroup-uniform up to the last barrier.
-template <int D, int NW>
+// WIDE: up to 128 query nodes per request (two mask words per node) instead of 64.
+template <int D, int NW, bool WIDE = false>
 __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg,
                                           int nchunks, int cb, int q0, int n, int ctx) {
   using C = AttnCfg<D>;
@@ -567,31 +573,38 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   const int t_end = min(L, t_begin + cb);
   const int ntiles = (t_end - t_begin + RC::kT - 1) / RC::kT;
 
-  unsigned long long* sh_anc = reinterpret_cast<unsigned long long*>(smem + 2 * RC::kStage);
-  int* sh_par = reinterpret_cast<int*>(smem + 2 * RC::kStage + 512);
-  int* sh_pages = reinterpret_cast<int*>(smem + 2 * RC::kStage + 768);      // [kMaxChunkPages]
+  constexpr int kNodes = WIDE ? kMaxQWide : kMaxQ;
+  constexpr int kWords = WIDE ? 2 : 1;
+  unsigned long long* sh_anc = reinterpret_cast<unsigned long long*>(smem + 2 * RC::kStage);          // [kNodes][kWords]
+  int* sh_par = reinterpret_cast<int*>(smem + 2 * RC::kStage + kNodes * kWords * 8);                  // [kNodes]
+  int* sh_pages = reinterpret_cast<int*>(smem + 2 * RC::kStage + RC::meta_bytes(WIDE));               // [kMaxChunkPages]
 
   const bool touches_drafts = t_end > ctx;
   if (touches_drafts) {
     if (P.parent) {
-      if (tid < kMaxQ) sh_par[tid] = (tid < n) ? P.parent[q0 + tid] : -1;
+      if (tid < kNodes) sh_par[tid] = (tid < n) ? P.parent[q0 + tid] : -1;
       __syncthreads();
     }
-    if (tid < kMaxQ) {
-      unsigned long long mask = 0;
+    if (tid < kNodes) {
+      unsigned long long mask = 0, mask_hi = 0;
       if (tid < n) {
         if (P.parent) {
           int a = tid;
           for (int g = 0; g <= tid && a >= 0; ++g) {
-            mask |= 1ull << a;
+            if (WIDE && a >= 64) mask_hi |= 1ull << (a - 64);
+            else mask |= 1ull << a;
             const int p = sh_par[a];
             a = (p >= a || p < -1) ? -1 : p;
           }
+        } else if (WIDE && tid >= 64) {
+          mask = ~0ull;
+          mask_hi = (2ull << (tid - 64)) - 1ull;
         } else {
           mask = (2ull << tid) - 1ull;
         }
       }
-      sh_anc[tid] = mask;
+      sh_anc[tid * kWords] = mask;
+      if (WIDE) sh_anc[tid * kWords + 1] = mask_hi;
     }
     __syncthreads();
   }
@@ -603,7 +616,8 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   const bool valid = row < R;
   const int node = valid ? row / P.G : 0;
   const int gq = valid ? row % P.G : 0;
-  const unsigned long long my_anc = (touches_drafts && valid) ? sh_anc[node] : 0ull;
+  const unsigned long long my_anc = (touches_drafts && valid) ? sh_anc[node * kWords] : 0ull;
+  const unsigned long long my_anc_hi = (WIDE && touches_drafts && valid) ? sh_anc[node * kWords + 1] : 0ull;
   const int64_t grow = static_cast<int64_t>(q0 + node) * P.Hq + kvh * P.G + gq;
   bf16x8 qf[C::kQKSteps];
   {
@@ -785,7 +799,8 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
         for (int r = 0; r < 16; ++r) {
           const int pos = tok0 + 32 * tb + 8 * (r >> 2) + 4 * lh + (r & 3);
           // branch-free on purpose: bitwise ops, no short-circuit control flow around the accumulator
-          const bool ok = (pos < ctx) | ((pos < L) & (((my_anc >> ((pos - ctx) & 63)) & 1ull) != 0ull));
+          const unsigned long long word = (WIDE && ((pos - ctx) & 64)) ? my_anc_hi : my_anc;
+          const bool ok = (pos < ctx) | ((pos < L) & (((word >> ((pos - ctx) & 63)) & 1ull) != 0ull));
           sacc[tb][r] = ok ? sacc[tb][r] : -INFINITY;
         }
     }
@@ -932,19 +947,19 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   }
 }
 
-template <int D, int NW>
+template <int D, int NW, bool WIDE>
 __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(AttnParams P) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int b = blockIdx.z;
   const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
   const int q0 = P.q_offsets[b];
   int n = P.q_offsets[b + 1] - q0;
-  n = n > kMaxQ ? kMaxQ : n;
+  n = n > (WIDE ? kMaxQWide : kMaxQ) ? (WIDE ? kMaxQWide : kMaxQ) : n;
   const int ctx = P.ctx_len[b];
   const int L = ctx + n;
   const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
   const int cb = (((L + nchunks - 1) / nchunks) + RowsCfg<D, NW>::kT - 1) & ~(RowsCfg<D, NW>::kT - 1);
-  rows_item<D, NW>(P, smem, b, blockIdx.y, chunk, rg, nchunks, cb, q0, n, ctx);
+  rows_item<D, NW, WIDE>(P, smem, b, blockIdx.y, chunk, rg, nchunks, cb, q0, n, ctx);
 }
 
 // Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
@@ -1029,7 +1044,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams P) {
   const int b = blockIdx.y;
   const int q0 = P.q_offsets[b];
   int n = P.q_offsets[b + 1] - q0;
-  n = n > kMaxQ ? kMaxQ : n;
+  n = n > P.n_cap ? P.n_cap : n;
   const int local = blockIdx.x * 8 + (threadIdx.x >> 5);
   if (local >= n * P.Hq) return;
   const int64_t grow = static_cast<int64_t>(q0) * P.Hq + local;
@@ -1084,6 +1099,7 @@ static long dev_knob(const char*, long fallback) { return fallback; }
 AttnPlan make_attn_plan(const AttnArgs& a) {
   AttnPlan p;
   p.tau = 0;
+  p.wide = a.max_q > kMaxQ ? 1 : 0;
   const int G = a.Hq / a.Hkv;
   const int max_rows = a.max_q * G;
   const int64_t max_tok0 = static_cast<int64_t>(a.max_pages) * a.page;
@@ -1099,6 +1115,8 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   if (force_kind == 1) { p.kind = 1; p.rows_per_wg = 128; }
   if (force_kind == 2 && a.D == 128) { p.kind = 2; p.rows_per_wg = 256; }
   if (force_kind == 0) { p.kind = 0; p.rows_per_wg = 128; }
+  // more than 64 query nodes per request (two mask words per node): the row-split kernels only
+  if (p.wide && p.kind == 0) { p.kind = 1; p.rows_per_wg = 128; }
   p.row_groups = (max_rows + p.rows_per_wg - 1) / p.rows_per_wg;
   const bool token_split = (p.kind == 0);
   const int gran = token_split ? kTile : 64;              // chunks are whole tiles
@@ -1187,14 +1205,21 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
+template <int D, int NW, bool WIDE>
+static int launch_rows_as(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
+  using RC = RowsCfg<D, NW>;
+  constexpr size_t kLds = RC::lds_bytes(WIDE);
+  static_assert(kLds * (NW == 4 ? 2 : 1) <= 160 * 1024, "row-split kernel: LDS per compute unit");
+  static std::atomic<uint64_t> attr_done{0};
+  if (set_lds_once(&attn_rows_kernel<D, NW, WIDE>, kLds, attr_done) != 0) return -6;
+  dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
+  hipLaunchKernelGGL((attn_rows_kernel<D, NW, WIDE>), grid, dim3(RC::kThreads), kLds, stream, P);
+  return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
 template <int D, int NW>
 static int launch_rows(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
-  using RC = RowsCfg<D, NW>;
-  static std::atomic<uint64_t> attr_done{0};
-  if (set_lds_once(&attn_rows_kernel<D, NW>, RC::kLds, attr_done) != 0) return -6;
-  dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
-  hipLaunchKernelGGL((attn_rows_kernel<D, NW>), grid, dim3(RC::kThreads), RC::kLds, stream, P);
-  return hipGetLastError() == hipSuccess ? 0 : -6;
+  return plan.wide ? launch_rows_as<D, NW, true>(P, plan, B, Hkv, stream) : launch_rows_as<D, NW, false>(P, plan, B, Hkv, stream);
 }
 
 int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
@@ -1214,6 +1239,7 @@ int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
   // work list: from 65 query rows per KV head (three 32-row blocks) on, a request runs the row-split body
   P.list_rows_min = plan.tau > 0 ? static_cast<int>(dev_knob("SPECV_ATTN_LIST_ROWS", 65)) : 0;
   P.list_rows_units = static_cast<int>(dev_knob("SPECV_ATTN_ROWS_UNITS", 4));
+  P.n_cap = plan.wide ? kMaxQWide : kMaxQ;
   P.c = a.scale * kLog2e;
   P.out_f32 = (a.out_dtype == kF32);
   int rc;
@@ -1222,7 +1248,7 @@ int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
   else rc = launch_rows<128, 8>(P, plan, a.B, a.Hkv, stream);
   if (rc != 0) return rc;
   if (plan.max_chunks > 1) {
-    const int max_q = a.max_q > kMaxQ ? kMaxQ : a.max_q;
+    const int max_q = a.max_q > P.n_cap ? P.n_cap : a.max_q;
     dim3 grid((max_q * a.Hq + 7) / 8, a.B);
     if (a.D == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, grid, dim3(256), 0, stream, P);
     else hipLaunchKernelGGL(attn_combine_kernel<64>, grid, dim3(256), 0, stream, P);

@@ -6,14 +6,14 @@
 // One workgroup per (request, KV head): the path is rebuilt from the parent array, every source row
 // (K and V, D 16-bit elements) is read into registers, a barrier, then the rows are written to their
 // destinations - destinations of one depth can be sources of another, so nothing is written before
-// everything is read.  Pure data movement: at most 64 rows of 2*D bytes per tensor, latency-bound.
+// everything is read.  Pure data movement: at most 128 rows of 2*D bytes per tensor, latency-bound.
 #include "common.h"
 #include "kernels.h"
 
 namespace specv {
 
 constexpr int kCompactThreads = 256;
-constexpr int kCompactMaxNodes = 64;
+constexpr int kCompactMaxNodes = 128;
 
 typedef uint32_t cu32x4 __attribute__((ext_vector_type(4)));
 

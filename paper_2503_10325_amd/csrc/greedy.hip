@@ -86,8 +86,9 @@ __global__ __launch_bounds__(kArgThreads) void row_argmax_kernel(const void* __r
   }
 }
 
-constexpr int kGreedyThreads = 128;
-constexpr int kGreedyMaxNodes = 64;
+constexpr int kGreedyThreads = 192;
+constexpr int kGreedyMaxNodes = 128;
+static_assert(kGreedyThreads > kGreedyMaxNodes, "one thread per target row of a request");
 
 __global__ __launch_bounds__(kGreedyThreads) void greedy_walk_kernel(
     int V, int nseg, const int32_t* __restrict__ node_offsets, const int32_t* __restrict__ parent,
@@ -111,20 +112,27 @@ __global__ __launch_bounds__(kGreedyThreads) void greedy_walk_kernel(
   }
   __syncthreads();
   if (tid >= kWave) return;
-  // lane j owns node j (lanes >= n hold an impossible parent)
-  int my_parent = -2, my_tok = -1;
-  if (lane < n) {
-    my_parent = parent ? parent[o + lane] : lane - 1;
-    if (my_parent < -1 || my_parent >= lane) my_parent = -1;      // same repair as the stochastic walk
-    my_tok = draft_tokens[o + lane];
+  // lane j owns nodes j and j + 64 (nodes that do not exist hold an impossible parent)
+  int my_parent[2] = {-2, -2}, my_tok[2] = {-1, -1};
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int node = lane + kWave * h;
+    if (node < n) {
+      int par = parent ? parent[o + node] : node - 1;
+      if (par < -1 || par >= node) par = -1;                      // same repair as the stochastic walk
+      my_parent[h] = par;
+      my_tok[h] = draft_tokens[o + node];
+    }
   }
   int cur = -1, depth = 0;
   for (int guard = 0; guard <= kGreedyMaxNodes; ++guard) {
     const int g = sh_arg[cur + 1];
     if (lane == 0 && depth < out_stride) out_tokens[static_cast<int64_t>(b) * out_stride + depth] = g;
-    const unsigned long long hit = __ballot(my_parent == cur && lane > cur && my_tok == g);
-    if (!hit) break;
-    cur = __ffsll(static_cast<long long>(hit)) - 1;
+    // the lowest-numbered child of the current node that proposes the argmax
+    const unsigned long long hit = __ballot(my_parent[0] == cur && lane > cur && my_tok[0] == g);
+    const unsigned long long hit_hi = __ballot(my_parent[1] == cur && lane + kWave > cur && my_tok[1] == g);
+    if (!(hit | hit_hi)) break;
+    cur = hit ? __ffsll(static_cast<long long>(hit)) - 1 : kWave + __ffsll(static_cast<long long>(hit_hi)) - 1;
     ++depth;
   }
   if (lane == 0) {

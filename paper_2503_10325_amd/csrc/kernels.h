@@ -162,6 +162,7 @@ struct AttnPlan {
   int chunk_tokens;
   int max_chunks;
   int tau;            // > 0: sorted-work-list launch of the token-split kernel, at most tau tiles per wave and item
+  int wide;           // more than 64 query nodes per request: kernels with two ancestor-mask words per node
 };
 AttnPlan make_attn_plan(const AttnArgs& a);
 size_t attn_workspace_bytes(const AttnArgs& a, const AttnPlan& plan);

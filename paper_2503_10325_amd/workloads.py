@@ -92,7 +92,11 @@ CONFIGS = {
                                         ("lognormal", 2048, 0.8, 512, 16384),
                                         ("linear_uniform", 2, 10), 128256, 3.0, ("noise", 1.0)),
 }
+# Secondary data point: c2 with the full 4,4,2,2 tree (4 + 16 + 32 + 64 = 116 nodes) instead of its first 64 nodes.
+CONFIGS["c2b_tree116_llama3_8b"] = dataclasses.replace(CONFIGS["c2_tree_llama3_8b"], name="c2b_tree116_llama3_8b",
+                                                       draft=("tree", (4, 4, 2, 2), 116))
 CONFIG_ORDER = ["c0_tiny", "c1_llama2_7b", "c2_tree_llama3_8b", "c3_fusion", "c4_llama70b_serving"]
+SECONDARY = ["c2b_tree116_llama3_8b"]
 
 
 def scaled(cfg: VerifyConfig, **overrides) -> VerifyConfig:

@@ -44,7 +44,7 @@ def test_attn_descriptor_validation_needs_no_gpu():
     assert call(sv.make_attn_desc(**{**ok, "num_kv_heads": 3})) == -2            # Hq % Hkv
     assert call(sv.make_attn_desc(**{**ok, "head_dim": 96})) == -3
     assert call(sv.make_attn_desc(**{**ok, "page_size": 32})) == -3
-    assert call(sv.make_attn_desc(**{**ok, "max_q_per_req": 65})) == -3
+    assert call(sv.make_attn_desc(**{**ok, "max_q_per_req": 129})) == -3
     assert call(sv.make_attn_desc(**{**ok, "batch": -1})) == -2
     assert call(sv.make_attn_desc(**{**ok, "batch": 0})) == 0                    # empty batch: nothing to do
     assert L.spec_verify_attn(None, null, null, null, null, null, null, null, null, null, null, 0, null) == -1
@@ -63,7 +63,7 @@ def test_accept_and_fuse_validation_needs_no_gpu():
     assert accept() == -1
     assert accept(V=0) == -2
     assert accept(T=0.0) == -2
-    assert accept(maxn=65, stride=66) == -3
+    assert accept(maxn=129, stride=130) == -3
     assert accept(stride=2) == -2
     assert accept(tdt=7) == -3
     assert accept(qk=2) == -3
@@ -92,7 +92,7 @@ def test_greedy_routing_adaptive_validation_needs_no_gpu():
 
     assert greedy() == -1                      # NULL tensors
     assert greedy(V=0) == -2
-    assert greedy(maxn=65, stride=66) == -3
+    assert greedy(maxn=129, stride=130) == -3
     assert greedy(stride=2) == -2
     assert greedy(tdt=5) == -3
     assert greedy(B=40000, total=40000) == -3  # more rows than one launch takes

@@ -41,11 +41,16 @@ def run(mods, a, stop, stop_dev=None):
     return not np.array_equal(k2, a.k_pool)
 
 
-@pytest.mark.parametrize("case", ["tree64_d128", "tree_small_d64", "linear", "none_accepted"])
+@pytest.mark.parametrize("case", ["tree64_d128", "tree116_d128", "tree_small_d64", "linear", "chain128", "none_accepted"])
 def test_compaction_matches_oracle(mods, case):
     rng = np.random.default_rng(7)
     if case == "tree64_d128":
         cfg = W.scaled(C["c2_tree_llama3_8b"], batch=5, n_q_heads=8, n_kv_heads=2, ctx=("uniform", 0, 300))
+    elif case == "tree116_d128":
+        cfg = W.scaled(C["c2_tree_llama3_8b"], batch=4, n_q_heads=4, n_kv_heads=2, ctx=("uniform", 0, 300),
+                       draft=("tree", (4, 4, 2, 2), 116))
+    elif case == "chain128":
+        cfg = W.scaled(C["c1_llama2_7b"], batch=3, n_q_heads=2, n_kv_heads=2, ctx=("uniform", 5, 200), draft=("linear", 128))
     elif case == "tree_small_d64":
         cfg = W.scaled(C["c0_tiny"], batch=6, n_q_heads=4, n_kv_heads=4, ctx=("uniform", 1, 90), draft=("tree", (3, 2, 2), 17))
     else:
@@ -54,8 +59,8 @@ def test_compaction_matches_oracle(mods, case):
     stop = np.array([rng.integers(-1, int(k)) for k in a.st.n], dtype=np.int32)
     if case == "none_accepted":
         stop[:] = -1
-    if case == "tree64_d128":
-        stop[0] = int(a.st.n[0]) - 1                     # a deepest leaf
+    if case in ("tree64_d128", "tree116_d128", "chain128"):
+        stop[0] = int(a.st.n[0]) - 1                     # a deepest leaf / the whole chain
     moved = run(mods, a, stop)
     assert moved == case.startswith("tree")
 

@@ -23,7 +23,7 @@ def rt():
     return runner
 
 
-@pytest.mark.parametrize("name", W.CONFIG_ORDER)
+@pytest.mark.parametrize("name", W.CONFIG_ORDER + W.SECONDARY)
 def test_fullsize_attention(rt, name):
     """Every request, every head, every draft node of the workload against the oracle."""
     cfg = W.CONFIGS[name]
@@ -50,7 +50,7 @@ def test_fullsize_attention(rt, name):
     assert np.abs(lse - ref_lse).max() < 2e-2
 
 
-@pytest.mark.parametrize("name", W.CONFIG_ORDER)
+@pytest.mark.parametrize("name", W.CONFIG_ORDER + W.SECONDARY)
 def test_fullsize_accept(rt, name):
     cfg = W.CONFIGS[name]
     st = W.make_structure(cfg, seed=0)

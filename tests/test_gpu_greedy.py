@@ -57,6 +57,13 @@ CASES = {
     "linear_odd_vocab": W.scaled(C["c1_llama2_7b"], batch=9, vocab=1001, draft=("linear_uniform", 1, 7)),
     "tree_v20000": W.scaled(C["c2_tree_llama3_8b"], batch=5, vocab=20000),
     "ragged_big_vocab": W.scaled(C["c4_llama70b_serving"], batch=5),
+    # more than 64 nodes per request
+    "tree116_v20000": W.scaled(C["c2_tree_llama3_8b"], batch=12, vocab=20000, draft=("tree", (4, 4, 2, 2), 116),
+                               q_src=("noise", 0.5)),
+    "tree126_deep": W.scaled(C["c2_tree_llama3_8b"], batch=12, vocab=20000, draft=("tree", (2, 2, 2, 2, 2, 2), 126),
+                             q_src=("noise", 0.5)),
+    "tree128_flat": W.scaled(C["c2_tree_llama3_8b"], batch=6, vocab=3000, draft=("tree", (40, 3), 128)),
+    "chain128": W.scaled(C["c1_llama2_7b"], batch=5, vocab=4000, draft=("linear_uniform", 60, 128), q_src=("noise", 0.05)),
 }
 
 
@@ -69,6 +76,8 @@ def test_greedy_matches_oracle(rt, name):
     print(f"{name}: mean accept_len {ref['accept_len'].mean():.2f}")
     if name != "tiny_full":
         assert ref["accept_len"].max() >= 1            # the case exercises real descents
+    if name in ("tree116_v20000", "tree126_deep"):
+        assert ref["stop_node"].max() >= 64            # ... into nodes held by the second ballot word
 
 
 def test_greedy_fp32_logits_ties_and_special_values(rt):
@@ -103,7 +112,7 @@ def test_greedy_zero_nodes_request(rt):
     check(rt, st, ai.target_logits, greedy_draft_tokens(st, ai))
 
 
-@pytest.mark.parametrize("name", W.CONFIG_ORDER)
+@pytest.mark.parametrize("name", W.CONFIG_ORDER + W.SECONDARY)
 def test_greedy_fullsize(rt, name):
     cfg = W.CONFIGS[name]
     st = W.make_structure(cfg, seed=0)

@@ -40,6 +40,16 @@ ATTN_CASES = {
                          draft=("linear_uniform", 1, 9)),
     "d64_rows_mixed": W.scaled(C["c0_tiny"], batch=5, n_q_heads=16, n_kv_heads=2, ctx=("uniform", 5, 3000),
                                draft=("linear_uniform", 2, 14)),
+    # more than 64 query nodes per request (two ancestor-mask words): the full 4,4,2,2 tree of Section 6.1's
+    # setting (116 nodes), a tree whose last node hangs under node 0, chains of up to 128 tokens, head_dim 64
+    "tree116_gqa4": W.scaled(C["c2_tree_llama3_8b"], batch=2, n_q_heads=8, n_kv_heads=2, ctx=("uniform", 100, 700),
+                             draft=("tree", (4, 4, 2, 2), 116)),
+    "tree128_flat": W.scaled(C["c2_tree_llama3_8b"], batch=2, n_q_heads=2, n_kv_heads=2, ctx=("uniform", 0, 200),
+                             draft=("tree", (64, 1), 128)),
+    "chain128_multi_chunk": W.scaled(C["c1_llama2_7b"], batch=3, n_q_heads=2, n_kv_heads=1, ctx=("uniform", 40, 5000),
+                                     draft=("linear_uniform", 60, 128)),
+    "tree100_d64": W.scaled(C["c0_tiny"], batch=3, n_q_heads=4, n_kv_heads=2, ctx=("uniform", 5, 600),
+                            draft=("tree", (3, 3, 3, 3), 100)),
     "ctx_zero": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=1, ctx=("fixed", 0), draft=("linear", 5)),
     "page_boundary": W.scaled(C["c1_llama2_7b"], batch=2, n_q_heads=2, n_kv_heads=2, ctx=("fixed", 56), draft=("linear", 8)),
 }
@@ -61,7 +71,8 @@ def test_attention_matches_oracle(rt, name):
     assert np.abs(lse - ref_lse).max() < 2e-2, f"{name}: lse err {np.abs(lse - ref_lse).max()}"
 
 
-@pytest.mark.parametrize("name", ["ragged_gqa8", "ragged_rows_mixed", "d64_rows_mixed", "d64_gqa2", "linear_multi_chunk", "tree_small_gqa"])
+@pytest.mark.parametrize("name", ["ragged_gqa8", "ragged_rows_mixed", "d64_rows_mixed", "d64_gqa2", "linear_multi_chunk", "tree_small_gqa",
+                                  "chain128_multi_chunk", "tree116_gqa4"])
 @pytest.mark.parametrize("hint", ["none", "exact", "small"])
 def test_attention_launch_modes(rt, name, hint):
     """The total-token hint only steers how the work is cut (grid-mapped chunks when it is absent or
@@ -144,6 +155,16 @@ ACCEPT_CASES = {
     "tree_wide": (W.scaled(C["c2_tree_llama3_8b"], batch=12, vocab=3000, draft=("tree", (5, 3), 20),
                            q_src=("noise", 2.0)), {}),
     "ragged_big_vocab": (W.scaled(C["c4_llama70b_serving"], batch=5), {}),
+    # more than 64 nodes per request: the full 4,4,2,2 tree (116 nodes), a flat tree whose nodes 64.. are
+    # children of low-numbered nodes, a chain of up to 128 tokens
+    "tree116_v20000": (W.scaled(C["c2_tree_llama3_8b"], batch=12, vocab=20000, draft=("tree", (4, 4, 2, 2), 116),
+                                q_src=("noise", 0.8)), {"deep": True}),
+    "tree126_deep": (W.scaled(C["c2_tree_llama3_8b"], batch=12, vocab=20000, draft=("tree", (2, 2, 2, 2, 2, 2), 126),
+                              q_src=("noise", 0.5)), {"deep": True}),
+    "tree128_flat": (W.scaled(C["c2_tree_llama3_8b"], batch=6, vocab=3000, draft=("tree", (40, 3), 128),
+                              q_src=("noise", 2.0)), {}),
+    "chain128": (W.scaled(C["c1_llama2_7b"], batch=5, vocab=4000, draft=("linear_uniform", 60, 128),
+                          q_src=("noise", 0.05)), {"deep": True}),
     "fp32_logits": (W.scaled(C["c1_llama2_7b"], batch=8, vocab=5000), {"fp32": True}),
     "temperature": (W.scaled(C["c1_llama2_7b"], batch=8, vocab=4096, temperature=0.7), {"fp32": True}),
 }
@@ -183,6 +204,8 @@ def test_accept_matches_oracle(rt, name, path):
     assert ties <= max(1, B // 4)
     assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
     assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
+    if opt.get("deep"):
+        assert ref["stop_node"].max() >= 64            # the walk reaches nodes of the second mask word
 
 
 LINEAR_CASES = {
