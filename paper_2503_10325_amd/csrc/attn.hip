@@ -71,6 +71,7 @@ struct AttnParams {
   int tau;           // > 0: a request is cut so that one wave streams at most tau tiles per work item
   int list_rows_min; // > 0 (work list only): requests with this many query rows per KV head use the row-split body
   int list_rows_units;
+  int xcd_swizzle;            // grid-mapped row-split launch: consecutive workgroups of the logical order share an XCD
   int n_cap;                  // query nodes per request the launched kernels handle (64, or 128 with two mask words)  // eighths of a work-list unit that 32 tokens of such a request cost
   float c;           // scale * log2(e)
   int out_f32;
@@ -950,8 +951,19 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
 template <int D, int NW, bool WIDE>
 __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(AttnParams P) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int b = blockIdx.z;
-  const int chunk = blockIdx.x % P.max_chunks, rg = blockIdx.x / P.max_chunks;
+  unsigned bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  if (P.xcd_swizzle) {
+    // Workgroups go to the 8 XCDs in turn.  With several row groups per (request, KV head) pair, renumber so that
+    // the row groups of a pair run on one XCD at the same time: the second read of the pair's K/V hits in that L2.
+    const unsigned total = gridDim.x * gridDim.y * gridDim.z;           // a multiple of 8 (checked by the host)
+    const unsigned linear = bx + gridDim.x * (by + gridDim.y * bz);
+    const unsigned logical = (linear % 8u) * (total / 8u) + linear / 8u;
+    bx = logical % gridDim.x;
+    by = (logical / gridDim.x) % gridDim.y;
+    bz = logical / (gridDim.x * gridDim.y);
+  }
+  const int b = static_cast<int>(bz);
+  const int chunk = static_cast<int>(bx) % P.max_chunks, rg = static_cast<int>(bx) / P.max_chunks;
   const int q0 = P.q_offsets[b];
   int n = P.q_offsets[b + 1] - q0;
   n = n > (WIDE ? kMaxQWide : kMaxQ) ? (WIDE ? kMaxQWide : kMaxQ) : n;
@@ -959,7 +971,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   const int L = ctx + n;
   const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
   const int cb = (((L + nchunks - 1) / nchunks) + RowsCfg<D, NW>::kT - 1) & ~(RowsCfg<D, NW>::kT - 1);
-  rows_item<D, NW, WIDE>(P, smem, b, blockIdx.y, chunk, rg, nchunks, cb, q0, n, ctx);
+  rows_item<D, NW, WIDE>(P, smem, b, static_cast<int>(by), chunk, rg, nchunks, cb, q0, n, ctx);
 }
 
 // Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
@@ -1240,6 +1252,8 @@ int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
   P.list_rows_min = plan.tau > 0 ? static_cast<int>(dev_knob("SPECV_ATTN_LIST_ROWS", 65)) : 0;
   P.list_rows_units = static_cast<int>(dev_knob("SPECV_ATTN_ROWS_UNITS", 4));
   P.n_cap = plan.wide ? kMaxQWide : kMaxQ;
+  P.xcd_swizzle = (plan.kind != 0 && plan.row_groups > 1 &&
+                   (static_cast<int64_t>(plan.max_chunks) * plan.row_groups * a.Hkv * a.B) % 8 == 0) ? 1 : 0;
   P.c = a.scale * kLog2e;
   P.out_f32 = (a.out_dtype == kF32);
   int rc;
