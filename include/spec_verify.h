@@ -152,8 +152,10 @@ int32_t spec_fuse_drafts(
  * is tried.  When the current node has no child (everything accepted) or all its
  * children were rejected, one token is drawn from r by inverse CDF in ascending
  * token order with u_resample[b]: the smallest t with sum_{v<=t} r_v > u * sum_v r_v.
- * For a linear draft this is exactly the rule of Section 2.1; siblings must be
- * i.i.d. draws from one draft row (they share q_row).  q(x)=0<r(x) accepts,
+ * For a linear draft this is exactly the rule of Section 2.1; the children of one
+ * node are i.i.d. draws from one draft row, the row the FIRST child's q_row entry
+ * names: it serves q(x_c) and the residual for every child of that node, and the
+ * q_row entries of later siblings are not used.  q(x)=0<r(x) accepts,
  * q(x)=r(x)=0 rejects; a residual of zero mass leaves r unchanged.
  * ---------------------------------------------------------------------------- */
 typedef enum { SPEC_Q_LOGITS = 0, SPEC_Q_PROBS = 1 } spec_q_kind;

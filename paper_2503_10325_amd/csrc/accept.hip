@@ -538,10 +538,12 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   __shared__ int sh_par[kMaxNodes], sh_tok[kMaxNodes], sh_qrow[kMaxNodes];
   __shared__ double sh_px[kMaxNodes], sh_qx[kMaxNodes];   // p_parent(x_j), q(x_j)
   __shared__ float sh_u[kMaxNodes];
+  __shared__ int sh_fc[kMaxNodes + 1];         // first child (lowest index) of node i at [i + 1]
 
   const bool q_is_probs = (P.q_kind == 1);
   const double u_res = static_cast<double>(P.u_resample[b]);      // needed last; fetched first
   // (1) node arrays
+  if (tid <= kMaxNodes) sh_fc[tid] = kMaxNodes;
   if (tid < n) {
     int par = P.parent ? P.parent[o + tid] : tid - 1;
     if (par < -1 || par >= tid) par = -1;
@@ -555,6 +557,17 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptParams 
   }
   if (tid < kMaxNodes) sh_inv_Rf[tid] = 0.f;
   __syncthreads();
+  if (P.parent) {
+    // The children of one node were drawn from one draft distribution: the row its first child names.  Every
+    // sibling uses that row (for q(x) and for the residual), whatever its own q_row entry says.
+    if (tid < n) atomicMin(&sh_fc[sh_par[tid] + 1], tid);
+    __syncthreads();
+    int group_row = 0;
+    if (tid < n) group_row = sh_qrow[min(sh_fc[sh_par[tid] + 1], kMaxNodes - 1)];
+    __syncthreads();
+    if (tid < n) sh_qrow[tid] = group_row;
+    __syncthreads();
+  }
   // (2) in one round trip: the two logits of every drafted token (last wave) and the merged
   // statistics of the n+1 target rows and n draft rows (groups of 16 lanes, one segment each)
   if (wave == kWalkWaves - 1) {

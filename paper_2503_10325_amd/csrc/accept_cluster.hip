@@ -219,12 +219,13 @@ __global__ __launch_bounds__(kClThreads) void accept_cluster_kernel(ClusterParam
   if (tid < n) atomicMin(&sh_fc[sh_par[tid] + 1], tid);      // first child = lowest index among the children
   // the two logits of every drafted token, kept in registers until the first round's loads are out
   float g_lp = 0.f, g_lq = 0.f;
-  if (tid < n) {
-    const int x = sh_tok[tid];
-    g_lp = bf16_bits_to_float(P.target[(trow0 + 1 + sh_par[tid]) * static_cast<int64_t>(V) + x]);
-    g_lq = bf16_bits_to_float(P.draft_q[static_cast<int64_t>(sh_qrow[tid]) * V + x]);
-  }
+  if (tid < n) g_lp = bf16_bits_to_float(P.target[(trow0 + 1 + sh_par[tid]) * static_cast<int64_t>(V) + sh_tok[tid]]);
   __syncthreads();
+  // the draft row of a sibling group is the one its first child names (the row the slices hold for that group)
+  if (tid < n) {
+    const int fc = min(sh_fc[sh_par[tid] + 1], kClNodes - 1);
+    g_lq = bf16_bits_to_float(P.draft_q[static_cast<int64_t>(sh_qrow[fc]) * V + sh_tok[tid]]);
+  }
   if (tid <= kClNodes && sh_fc[tid] >= kClNodes) sh_fc[tid] = -2;   // no child
   __syncthreads();
   // lane l looks after nodes l and l + 64; nodes that do not exist hold an impossible parent

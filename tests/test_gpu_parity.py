@@ -411,6 +411,40 @@ def test_accept_with_probability_rows(rt):
     assert not bad
 
 
+@pytest.mark.parametrize("path", [0, 1, 2])
+def test_accept_sibling_group_takes_its_first_childs_draft_row(rt, path):
+    """The children of one node are draws from one draft distribution, the row their first child names (the
+    reading the oracle implements).  Later siblings whose q_row entries name other rows change nothing: the
+    kernels, like the oracle, use the group's row for q(x) and for the residual."""
+    import dataclasses
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=6, vocab=20000, q_src=("noise", 1.5))
+    ai = W.make_accept_inputs(cfg, seed=13)
+    st = ai.st
+    n_q_rows = ai.draft_q.shape[0]
+    q_row = ai.q_row.copy()
+    seen, changed = set(), 0
+    for b in range(cfg.batch):
+        o = int(st.node_offsets[b])
+        for j in range(int(st.n[b])):
+            key = (b, int(st.parent[o + j]))
+            if key in seen:                               # not the first child of its parent
+                q_row[o + j] = (int(q_row[o + j]) + 1 + 7 * j) % n_q_rows
+                changed += 1
+            seen.add(key)
+    assert changed > 0
+    ai2 = dataclasses.replace(ai, q_row=q_row)
+    got, ref = _run_accept(rt, cfg, ai2, tuning=_tuning(path=path) if path else None)
+    ref0 = oracle.accept(st.node_offsets, st.parent, ai.draft_tokens, ai.target_logits, ai.draft_q, ai.q_row,
+                         ai.u_accept, ai.u_resample, temperature=cfg.temperature, qkind=0)
+    for k in ("accept_len", "out_tokens", "stop_node"):
+        assert np.array_equal(ref[k], ref0[k])            # the oracle ignores the later siblings' entries
+    assert (ref["accept_len"] > 0).any() and np.isfinite(ref["ratio"]).sum() > 2 * cfg.batch   # siblings were tried
+    bad, ties, B = compare_accept(got, ref, st.n)
+    assert not bad, f"requests {bad} differ outside near-ties"
+    assert ratio_err(got["ratio"], ref["ratio"]) < 5e-6
+    assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
+
+
 @pytest.mark.parametrize("path", [0, 1, 3, 4])
 def test_accept_zero_nodes_request(rt, path):
     cfg = W.scaled(C["c1_llama2_7b"], batch=4, vocab=1000, draft=("linear", 3))
