@@ -384,9 +384,16 @@ def measure(name, args, cpu_seconds):
     if args.accept_mode == "greedy":
         accept_plan = "row_argmax_kernel + greedy_walk_kernel"
     elif lm is not None:
-        accept_plan = ("row_stats_kernel (draft rows only) + " +
-                       ("accept_linear_kernel" if a.st.parent is None else "accept_walk_kernel") +
-                       ", target statistics from spec_lm_head")
+        # (spec_accept_prestats: what the library would pick for spec_accept, minus the target rows' statistics;
+        # the kernel that reads only the walked rows of a tree takes its statistics itself)
+        plain = sv.spec_describe_accept_plan(cfg.batch, cfg.vocab, int(a.st.total), int(a.st.n.max()), a.st.parent is not None,
+                                             q_kind=c0.accept.q_kind, q_dtype=sv._dtype_code(c0.accept.draft_q))
+        if "accept_cluster_kernel" in plain:
+            accept_plan = plain + " (statistics from spec_lm_head not needed)"
+        else:
+            accept_plan = ("row_stats_kernel (draft rows only) + " +
+                           ("accept_linear_kernel" if a.st.parent is None else "accept_walk_kernel") +
+                           ", target statistics from spec_lm_head")
     else:
         accept_plan = sv.spec_describe_accept_plan(cfg.batch, cfg.vocab, int(a.st.total), int(a.st.n.max()), a.st.parent is not None,
                                                    q_kind=c0.accept.q_kind, q_dtype=sv._dtype_code(c0.accept.draft_q),

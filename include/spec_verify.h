@@ -392,6 +392,8 @@ int32_t spec_lm_head(
  * results, but the first spec_row_stats_size(total_nodes + B, V) bytes of workspace
  * already hold the target rows' statistics (written by spec_lm_head with the same
  * temperature, V and row order), so only the draft rows are read for statistics.
+ * (Draft trees for which the library picks the kernel that reads only the walked rows
+ * are verified from the logits alone; the supplied statistics are then not read.)
  * target_dtype must be SPEC_BF16.  Workspace size as for spec_accept.
  * ---------------------------------------------------------------------------- */
 int32_t spec_accept_prestats(

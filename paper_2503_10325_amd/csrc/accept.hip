@@ -1181,7 +1181,7 @@ static bool progressive_stats(const AcceptArgs& a) {
 const char* accept_plan_name(const AcceptArgs& a, int n_cu) {
   const bool vec = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
   const bool cluster_ok = vec && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
-                          a.q_kind == 0 && !a.target_stats_ready;
+                          a.q_kind == 0;
   const bool cluster = cluster_ok && (a.path == 2 || (a.path == 0 && a.parent != nullptr && cluster_pays(a.B, a.V, n_cu)));
   if (!cluster && progressive_stats(a)) return "row_stats_prog_kernel (rows up to each request's first rejection) + accept_linear_kernel (linear drafts: one vocabulary unit per workgroup, the last to arrive draws)";
   if (!cluster && linear_path(a)) return "row_stats_kernel (all rows) + accept_linear_kernel (linear drafts: one vocabulary unit per workgroup, the last to arrive draws)";
@@ -1200,10 +1200,11 @@ void launch_accept(const AcceptArgs& a, hipStream_t stream) {
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
   const int n_cu = current_device_cus();
   {
-    // bf16 logit rows (the default layout): one kernel that reads only the rows the walk reaches
+    // bf16 logit rows (the default layout): one kernel that reads only the rows the walk reaches (it takes the
+    // statistics of those rows itself; target statistics a caller supplies are not needed then)
     const bool vec0 = (a.V % 8 == 0) && aligned16(a.target) && aligned16(a.draft_q);
     const bool cluster_ok = vec0 && a.V >= 8 && a.V <= kClusterMaxV && a.t_dtype == kBF16 && a.q_dtype == kBF16 &&
-                            a.q_kind == 0 && !a.target_stats_ready;
+                            a.q_kind == 0;
     if (cluster_ok && (a.path == 2 || (a.path == 0 && a.parent != nullptr && cluster_pays(a.B, a.V, n_cu)))) {
       const ClusterPlan plan = make_cluster_plan(a.B, a.V, a.max_nodes, a.parent != nullptr, n_cu, a.levels, a.slices);
       launch_accept_cluster(a, plan, a.patience >= 0 ? a.patience : 4000, ws + lay.msg_off, stream);

@@ -445,6 +445,26 @@ def test_accept_sibling_group_takes_its_first_childs_draft_row(rt, path):
     assert np.array_equal(np.isnan(got["ratio"]), np.isnan(ref["ratio"]))
 
 
+def test_accept_prestats_on_a_tree_the_cluster_kernel_takes(rt):
+    """spec_accept_prestats on a shape for which the library picks the cluster kernel: that kernel takes the
+    statistics of the walked rows itself, so the statistics region of the workspace is not read (it holds NaN
+    patterns here) and the results are those of spec_accept, and the oracle's."""
+    from paper_2503_10325_amd import binding as sv
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=4, vocab=65536)
+    ai = W.make_accept_inputs(cfg, seed=21)
+    assert "accept_cluster_kernel" in sv.spec_describe_accept_plan(cfg.batch, cfg.vocab, ai.st.total, int(ai.st.n.max()), True)
+    got, ref = _run_accept(rt, cfg, ai)
+    dev = rt.DeviceAccept(ai.st, ai.target_logits, ai.draft_q, ai.q_row, ai.draft_tokens, ai.u_accept, ai.u_resample,
+                          temperature=cfg.temperature)
+    dev.workspace.fill_(0xFF)
+    dev.run_prestats()
+    pre = dev.results()
+    for key in ("accept_len", "out_tokens", "stop_node"):
+        assert np.array_equal(pre[key], got[key]), key
+    bad, _, _ = compare_accept(pre, ref, ai.st.n)
+    assert not bad
+
+
 @pytest.mark.parametrize("path", [0, 1, 3, 4])
 def test_accept_zero_nodes_request(rt, path):
     cfg = W.scaled(C["c1_llama2_7b"], batch=4, vocab=1000, draft=("linear", 3))
