@@ -12,6 +12,12 @@
 //                         over the waves of up to three helper workgroups.
 //   accept_linear_kernel  linear drafts: the scalar tests repeated in every workgroup, the one
 //                         vocabulary-wide draw spread over several workgroups per request.
+//   row_stats_prog_kernel large batches of linear drafts: the statistics pass in chain order, with
+//                         the accept decisions taken on the way, so that rows behind a request's
+//                         first rejection are not read.
+// (accept_cluster.hip holds the tree kernel that reads only the rows a walk reaches.)
+// Up to 128 draft nodes per request; the children of one node share one draft row, the one the
+// first child names.
 #include "common.h"
 #include "kernels.h"
 

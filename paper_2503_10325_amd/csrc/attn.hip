@@ -11,9 +11,10 @@
 //     operands; waves that share a 32-row query block merge through LDS.  Launched grid-mapped
 //     (attn_stream_kernel) or, for small ragged batches, from a work list built on the device and
 //     sorted by length (attn_stream_list_kernel).
-//   row-split (attn_rows_kernel, more rows): the 4 or 8 waves of a workgroup stage 64-token
-//     tiles together (double-buffered LDS, two tiles of global loads in flight) and each owns
-//     one block of 32 query rows.
+//   row-split (rows_item; attn_rows_kernel, more rows, and inside the work list): the 4 or 8 waves of a
+//     workgroup stage 64-token tiles together (double-buffered LDS; with 8 waves two tiles of global
+//     loads in flight) and each owns one block of 32 query rows.  Instantiated a second time for
+//     requests of 65 to 128 draft nodes (two ancestor-mask words per node).
 // In both, S^T = K Q^T runs on v_mfma_f32_32x32x16_bf16 with the tokens as the M dimension, so
 // each lane owns one query column and the online-softmax statistics need a single exchange
 // between the half-waves.  V is transposed on its way into LDS (token pairs packed with v_perm).
@@ -977,8 +978,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
 // Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
 // is two workgroups per compute unit; every workgroup derives the same list of work items
 // (request, chunk, KV head) from the lengths on the device, ordered by decreasing number of tiles
-// a wave streams per item, and takes items blockIdx.x, blockIdx.x + gridDim.x, ...: long items
-// start first, short ones fill the tail, and no workgroup is launched for chunks that do not exist.
+// a wave streams per item, and takes one item per round of gridDim.x items (in workgroup order on even
+// rounds, reversed on odd ones): long items start first, short ones fill the tail, and no workgroup is
+// launched for chunks that do not exist.
 // An item runs the token-split body or, for requests with many query rows, the row-split body.
 template <int D>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_stream_list_kernel(AttnParams P) {
