@@ -35,6 +35,11 @@ constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = 4;
 constexpr int kTile = 32;          // tokens per wave iteration
 constexpr int kPage = 16;
+// Head dimension of row m (0..31) of accumulator block db of O^T = V^T P^T: the V^T rows are stored by
+// (d%8, d/8), see AttnCfg, and read in storage order.  With a = r >> 2, c = r & 3 of accumulator register r and
+// the lane's half lh, m = 8a + 4lh + c; the registers (db, a) with equal (a % A, c), A = D/64, hold 8 consecutive
+// head dimensions from acc_dim0<D>(a % A, c, lh) on, in the order j = (32*8/D) * db + a / A.
+template <int D> __device__ __forceinline__ constexpr int acc_dim0(int am, int c, int lh) { return 8 * (8 * am + 4 * lh + c); }
 constexpr int kMaxQ = 64;             // query nodes per request with one ancestor-mask word
 constexpr int kMaxQWide = 128;        // ... with two (row-split kernels only)
 
@@ -46,7 +51,10 @@ struct AttnCfg {
   static constexpr int kKStride = D * 2 + 16;             // bytes; padded K row in LDS
   static constexpr int kKBytes = kTile * kKStride;
   static constexpr int kVStride = 80;                     // bytes; one V^T row = 32 tokens + pad
-  static constexpr int kVRows = 7 * 18 + D / 8;           // row index sigma(d) = (d%8)*18 + d/8
+  // V^T row of head dimension d: sigma(d) = (d%8)*(D/8) + d/8.  Lane ln of the output product's block db reads
+  // row 32*db + ln - consecutive rows, free of LDS bank conflicts at this stride (an odd multiple of 16 bytes) -
+  // so accumulator row m of block db belongs to head dimension acc_dim<D>(db, m): see there.
+  static constexpr int kVRows = D;
   static constexpr int kVBytes = kVRows * kVStride;
   static constexpr int kWaveLds = kKBytes + kVBytes;
   static constexpr int kQKSteps = D / 16;
@@ -358,7 +366,7 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
           uint2 o;
           o.x = __builtin_amdgcn_perm(w1[k], w0[k], sel);    // tokens 4va, 4va+1 at dim 8kc+2k+half
           o.y = __builtin_amdgcn_perm(w3[k], w2[k], sel);    // tokens 4va+2, 4va+3
-          const int vrow = (2 * k + half) * 18 + kc;
+          const int vrow = (2 * k + half) * (D / 8) + kc;
           *reinterpret_cast<uint2*>(v_lds + vrow * C::kVStride + 32 * s + 16 * vhh + 8 * vpart) = o;
         }
       }
@@ -424,8 +432,7 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
       const bf16x8 phi = __builtin_bit_cast(bf16x8, hi), plo = __builtin_bit_cast(bf16x8, lo);
 #pragma unroll
       for (int db = 0; db < C::kDBlocks; ++db) {
-        const int d = 32 * db + ln;
-        const int vrow = (d & 7) * 18 + (d >> 3);
+        const int vrow = 32 * db + ln;           // storage order: head dimension acc_dim of this lane
         const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(v_lds + vrow * C::kVStride + 32 * s + 16 * lh));
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, phi, oacc[db], 0, 0, 0);
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plo, oacc[db], 0, 0, 0);
@@ -450,19 +457,18 @@ __device__ __forceinline__ void stream_item(const AttnParams& P, unsigned char* 
 
   float* sh_o = reinterpret_cast<float*>(smem);        // [4 waves][32][kORedStride]
   if (wave_active) {
+    constexpr int kA = D / 64, kQ = 256 / D;     // see acc_dim0
 #pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db) {
+    for (int am = 0; am < kA; ++am)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        float4 v;
-        v.x = oacc[db][4 * r4 + 0] * fscale;
-        v.y = oacc[db][4 * r4 + 1] * fscale;
-        v.z = oacc[db][4 * r4 + 2] * fscale;
-        v.w = oacc[db][4 * r4 + 3] * fscale;
-        const int d = 32 * db + 8 * r4 + 4 * lh;
-        *reinterpret_cast<float4*>(sh_o + (wave * 32 + ln) * C::kORedStride + d) = v;
+      for (int c = 0; c < 4; ++c) {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = oacc[j / kQ][4 * ((j % kQ) * kA + am) + c] * fscale;
+        float* dst = sh_o + (wave * 32 + ln) * C::kORedStride + acc_dim0<D>(am, c, lh);
+        *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4*>(dst + 4) = make_float4(x[4], x[5], x[6], x[7]);
       }
-    }
   }
   __syncthreads();
   const int rn = tid >> 3;                               // query column this thread finalises
@@ -539,7 +545,7 @@ struct RowsCfg {
   static constexpr int kKStride = D * 2 + 16;
   static constexpr int kKBytes = kT * kKStride;
   static constexpr int kVStride = kT * 2 + 16;
-  static constexpr int kVRows = 7 * 18 + D / 8;
+  static constexpr int kVRows = D;                         // rows in storage order, see AttnCfg
   static constexpr int kVBytes = kVRows * kVStride;
   static constexpr int kStage = kKBytes + kVBytes;
   static constexpr int kMaxChunkPages = NW == 8 ? 1024 : 512;   // a chunk spans at most 16384 (8192) tokens
@@ -723,7 +729,7 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         const uint32_t sel = half ? 0x07060302u : 0x05040100u;
-        const int vrow = (2 * k + half) * 18 + vc;
+        const int vrow = (2 * k + half) * (D / 8) + vc;
         unsigned char* dst = v_lds + vrow * RC::kVStride + col;
         if constexpr (RC::kTpt == 4) {
           const uint32_t w2k = vr[2][k], w3k = vr[3][k];
@@ -743,8 +749,8 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   f16x8 ph, va[C::kDBlocks];
   float m_safe = 0.f, m_next = -INFINITY, alpha = 1.f, psum = 0.f;
   auto v_frag = [&](int stage, int chunk, int db) {      // chunk = 16-token group 0..3 of the tile
-    const unsigned char* v_rd = smem + stage * RC::kStage + RC::kKBytes + ((ln & 7) * 18 + (ln >> 3)) * RC::kVStride + 16 * lh;
-    return __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(v_rd + 4 * db * RC::kVStride + 32 * chunk));
+    const unsigned char* v_rd = smem + stage * RC::kStage + RC::kKBytes + ln * RC::kVStride + 16 * lh;
+    return __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(v_rd + 32 * db * RC::kVStride + 32 * chunk));
   };
   // P^T as fp16 (weights lie in [0, 2^8]: 11 significant bits, against 8 of bf16, keep the output's error at the
   // level of its own bf16 rounding with a single matrix term), 16 tokens at a time
@@ -915,37 +921,36 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   // [0, 2^-11], 2^-12 on average, while the denominator l was summed from the unrounded weights.  The
   // average is put back here; what remains is the zero-mean part (2^-12 at most per weight).
   constexpr float kRtzFix = 1.f + 1.f / 4096.f;
+  // eight consecutive head dimensions at a time (acc_dim0)
+  constexpr int kA = D / 64, kQ = 256 / D;
+  const float oscale = nchunks == 1 ? kRtzFix / l_run : kRtzFix;
+  float* part = P.ws_o + (grow * P.max_chunks + chunk) * D;
+#pragma unroll
+  for (int am = 0; am < kA; ++am)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = oacc[j / kQ][4 * ((j % kQ) * kA + am) + c] * oscale;
+      const int d = acc_dim0<D>(am, c, lh);
+      if (nchunks != 1) {
+        *reinterpret_cast<float4*>(part + d) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4*>(part + d + 4) = make_float4(x[4], x[5], x[6], x[7]);
+      } else if (P.out_f32) {
+        float* o = static_cast<float*>(P.out) + grow * D + d;
+        *reinterpret_cast<float4*>(o) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4*>(o + 4) = make_float4(x[4], x[5], x[6], x[7]);
+      } else {
+        u32x4 o;
+        o[0] = pack_bf16(x[0], x[1]); o[1] = pack_bf16(x[2], x[3]);
+        o[2] = pack_bf16(x[4], x[5]); o[3] = pack_bf16(x[6], x[7]);
+        *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(P.out) + grow * D + d) = o;
+      }
+    }
   if (nchunks == 1) {
-    const float inv = kRtzFix / l_run;
-#pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int d = 32 * db + 8 * r4 + 4 * lh;
-        const float x0 = oacc[db][4 * r4] * inv, x1 = oacc[db][4 * r4 + 1] * inv;
-        const float x2 = oacc[db][4 * r4 + 2] * inv, x3 = oacc[db][4 * r4 + 3] * inv;
-        if (P.out_f32) {
-          *reinterpret_cast<float4*>(static_cast<float*>(P.out) + grow * D + d) = make_float4(x0, x1, x2, x3);
-        } else {
-          uint2 o;
-          o.x = pack_bf16(x0, x1);
-          o.y = pack_bf16(x2, x3);
-          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(P.out) + grow * D + d) = o;
-        }
-      }
     if (P.lse && lh == 0) P.lse[grow] = (m_run + log2f(l_run)) * static_cast<float>(kLn2);
-  } else {
-    float* o = P.ws_o + (grow * P.max_chunks + chunk) * D;
-#pragma unroll
-    for (int db = 0; db < C::kDBlocks; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int d = 32 * db + 8 * r4 + 4 * lh;
-        *reinterpret_cast<float4*>(o + d) =
-            make_float4(oacc[db][4 * r4] * kRtzFix, oacc[db][4 * r4 + 1] * kRtzFix,
-                        oacc[db][4 * r4 + 2] * kRtzFix, oacc[db][4 * r4 + 3] * kRtzFix);
-      }
-    if (lh == 0) P.ws_ml[grow * P.max_chunks + chunk] = make_float2(m_run, l_run);
+  } else if (lh == 0) {
+    P.ws_ml[grow * P.max_chunks + chunk] = make_float2(m_run, l_run);
   }
 }
 
