@@ -933,13 +933,19 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
 #pragma unroll
       for (int j = 0; j < 8; ++j) x[j] = oacc[j / kQ][4 * ((j % kQ) * kA + am) + c] * oscale;
       const int d = acc_dim0<D>(am, c, lh);
-      if (nchunks != 1) {
-        *reinterpret_cast<float4*>(part + d) = make_float4(x[0], x[1], x[2], x[3]);
-        *reinterpret_cast<float4*>(part + d + 4) = make_float4(x[4], x[5], x[6], x[7]);
-      } else if (P.out_f32) {
-        float* o = static_cast<float*>(P.out) + grow * D + d;
-        *reinterpret_cast<float4*>(o) = make_float4(x[0], x[1], x[2], x[3]);
-        *reinterpret_cast<float4*>(o + 4) = make_float4(x[4], x[5], x[6], x[7]);
+      if (nchunks != 1 || P.out_f32) {
+        // fp32 rows: the two half-waves exchange halves of their eight values, so that one store instruction
+        // writes 32 contiguous bytes per row (lane ln: 16 bytes, lane ln + 32: the next 16) instead of 16
+        float lo4[4], hi4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[i]), __float_as_uint(x[4 + i]), false, false);
+          lo4[i] = __uint_as_float(r[0]);          // dims d0 .. of the lower half-wave's group: first / second four
+          hi4[i] = __uint_as_float(r[1]);          // dims d0 .. of the upper half-wave's group
+        }
+        float* o = (nchunks != 1 ? part : static_cast<float*>(P.out) + grow * D) + acc_dim0<D>(am, c, 0) + 4 * lh;
+        *reinterpret_cast<float4*>(o) = make_float4(lo4[0], lo4[1], lo4[2], lo4[3]);
+        *reinterpret_cast<float4*>(o + 32) = make_float4(hi4[0], hi4[1], hi4[2], hi4[3]);
       } else {
         u32x4 o;
         o[0] = pack_bf16(x[0], x[1]); o[1] = pack_bf16(x[2], x[3]);
