@@ -63,6 +63,44 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
   return u >> 16;
 }
 
+// Store the 32 vocabulary entries [vt, vt + 32) of one accumulator tile for this lane's row.  b[4 g + i] holds the
+// lane's entry 8 g + 4 lh + i as bf16 bits.  full (uniform over the wave): the tile lies inside V, V is a multiple
+// of 8 and the logits are 16-byte aligned; the two half-waves then exchange halves (lane ln ends up with all eight
+// entries of group 2h, lane ln + 32 with those of group 2h + 1), so that every lane stores 16 bytes and one
+// instruction writes 32 contiguous bytes per row - 8-byte stores left half of every 32-byte sector to a later
+// instruction.
+__device__ __forceinline__ void store_logit_tile(uint16_t* __restrict__ out_row, int vt, int lh, const uint32_t (&b)[16],
+                                                 bool row_ok, bool full, int V) {
+  if (full) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t w0x = b[8 * h + 0] | (b[8 * h + 1] << 16), w0y = b[8 * h + 2] | (b[8 * h + 3] << 16);
+      const uint32_t w1x = b[8 * h + 4] | (b[8 * h + 5] << 16), w1y = b[8 * h + 6] | (b[8 * h + 7] << 16);
+      const auto rx = __builtin_amdgcn_permlane32_swap(w0x, w1x, false, false);
+      const auto ry = __builtin_amdgcn_permlane32_swap(w0y, w1y, false, false);
+      lm_u32x4 v;
+      v[0] = rx[0]; v[1] = ry[0]; v[2] = rx[1]; v[3] = ry[1];
+      if (row_ok) *reinterpret_cast<lm_u32x4*>(out_row + vt + 8 * (2 * h + lh)) = v;
+    }
+  } else if (row_ok) {
+    const bool vec4 = (V & 3) == 0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int vg = vt + 8 * g + 4 * lh;
+      if (vec4 && vg + 3 < V) {
+        lm_u32x2 w;
+        w.x = b[4 * g] | (b[4 * g + 1] << 16);
+        w.y = b[4 * g + 2] | (b[4 * g + 3] << 16);
+        *reinterpret_cast<lm_u32x2*>(out_row + vg) = w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (vg + i < V) out_row[vg + i] = static_cast<uint16_t>(b[4 * g + i]);
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
   extern __shared__ __align__(16) unsigned char lm_lds[];
   // consecutive logical blocks (the row blocks of one vocabulary block) on one XCD
@@ -168,38 +206,27 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_kernel(LmParams P) {
   __syncthreads();
   float2* sh_stat = reinterpret_cast<float2*>(lm_lds + kLmHidBytes);     // [4 tiles][128 rows]
   if (kh == 0) {
-    const bool vec4 = (P.V & 3) == 0;
+    const bool full = (P.V & 7) == 0 && v0 + 32 <= P.V && (reinterpret_cast<uintptr_t>(P.logits) & 15) == 0;
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
       const int row = r0 + nt * 32 + ln;
       const bool row_ok = row < P.rows;
       uint16_t* out = P.logits + static_cast<int64_t>(row_ok ? row : 0) * P.V;
       float x[16];
+      uint32_t b[16];
       float m = -INFINITY;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int vg = v0 + 8 * g + 4 * lh;
-        uint32_t b[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = 4 * g + i;
-          b[i] = f32_to_bf16_rne(acc[nt][r] + red[((mt * 64 + nt * 16 + r) << 6) + lane]);
-          x[r] = (vg + i < P.V) ? __uint_as_float(b[i] << 16) : -INFINITY;
+          b[r] = f32_to_bf16_rne(acc[nt][r] + red[((mt * 64 + nt * 16 + r) << 6) + lane]);
+          x[r] = (vg + i < P.V) ? __uint_as_float(b[r] << 16) : -INFINITY;
           m = fmaxf(m, x[r]);
         }
-        if (row_ok) {
-          if (vec4 && vg + 3 < P.V) {
-            lm_u32x2 w;
-            w.x = b[0] | (b[1] << 16);
-            w.y = b[2] | (b[3] << 16);
-            *reinterpret_cast<lm_u32x2*>(out + vg) = w;
-          } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (vg + i < P.V) out[vg + i] = static_cast<uint16_t>(b[i]);
-          }
-        }
       }
+      store_logit_tile(out, v0, lh, b, row_ok, full, P.V);
       const float mm = (m == -INFINITY) ? 0.f : m;
       float s = 0.f;
 #pragma unroll
@@ -497,7 +524,7 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
   }
 
   // each wave holds all 128 vocabulary entries of the block for its rows: statistics need no LDS
-  const bool vec4 = (P.V & 3) == 0;
+  const bool aligned = (P.V & 7) == 0 && (reinterpret_cast<uintptr_t>(P.logits) & 15) == 0;
 #pragma unroll
   for (int ni = 0; ni < 2; ++ni) {
     const int row = r0 + ni * 32 + ln;
@@ -507,30 +534,19 @@ __global__ __launch_bounds__(kLwThreads) void lm_head_wide_kernel(LmParams P, co
     float x[4][16];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
+      uint32_t b[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int vg = v0 + 32 * mi + 8 * g + 4 * lh;
-        uint32_t b[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = 4 * g + i;
-          b[i] = f32_to_bf16_rne(acc[mi][ni][r]);
-          x[mi][r] = (vg + i < P.V) ? __uint_as_float(b[i] << 16) : -INFINITY;
+          b[r] = f32_to_bf16_rne(acc[mi][ni][r]);
+          x[mi][r] = (vg + i < P.V) ? __uint_as_float(b[r] << 16) : -INFINITY;
           m = fmaxf(m, x[mi][r]);
         }
-        if (row_ok) {
-          if (vec4 && vg + 3 < P.V) {
-            lm_u32x2 w;
-            w.x = b[0] | (b[1] << 16);
-            w.y = b[2] | (b[3] << 16);
-            *reinterpret_cast<lm_u32x2*>(out + vg) = w;
-          } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (vg + i < P.V) out[vg + i] = static_cast<uint16_t>(b[i]);
-          }
-        }
       }
+      store_logit_tile(out, v0 + 32 * mi, lh, b, row_ok, aligned && v0 + 32 * mi + 32 <= P.V, P.V);
     }
     const float mm = (m == -INFINITY) ? 0.f : m;
     float s = 0.f;
