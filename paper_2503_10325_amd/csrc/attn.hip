@@ -535,9 +535,14 @@ constexpr int kPlanMaxB = 128;
 // cooperatively (double-buffered in LDS) and every wave owns one block of 32 query rows,
 // for which it sees every token: no cross-wave merge is needed.
 // ----------------------------------------------------------------------------------
-template <int D, int NW>
+// SL = 2 ("sliced"): the workgroup owns 32 * NW / 2 query rows and stages 128-token tiles; waves w and w + NW/2
+// share a block of 32 rows, the first computing the lower 64 tokens of every staged tile, the second the upper 64,
+// and they merge their results through LDS at the end.  It fills the chip from half as many (request, KV head,
+// 256-row group) triples as SL = 1 without cutting the context (no partial results in memory, no combine kernel).
+template <int D, int NW, int SL = 1>
 struct RowsCfg {
-  static constexpr int kT = 64;                            // tokens per tile
+  static constexpr int kTc = 64;                           // tokens one wave computes per step
+  static constexpr int kT = kTc * SL;                      // tokens per staged tile
   static constexpr int kThreads = NW * 64;
   static constexpr int kCh = D / 8;
   static constexpr int kLoads = kT * kCh / kThreads;       // 16-byte loads per thread per tensor
@@ -560,12 +565,13 @@ struct RowsCfg {
 // One work item of the row-split body: (request b, KV head kvh, context chunk `chunk` of `nchunks`, row group
 // rg).  The request's context is cut into nchunks pieces of cb tokens (a multiple of the tile).  Every return
 // below is workgroup-uniform up to the last barrier.
-// WIDE: up to 128 query nodes per request (two mask words per node) instead of 64.
-template <int D, int NW, bool WIDE = false>
+// WIDE: up to 128 query nodes per request (two mask words per node) instead of 64.  SL: see RowsCfg.
+template <int D, int NW, bool WIDE = false, int SL = 1>
 __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* smem, int b, int kvh, int chunk, int rg,
                                           int nchunks, int cb, int q0, int n, int ctx) {
   using C = AttnCfg<D>;
-  using RC = RowsCfg<D, NW>;
+  using RC = RowsCfg<D, NW, SL>;
+  constexpr int kRowWaves = NW / SL;            // waves with row blocks of their own
   const int tid = static_cast<int>(threadIdx.x) + opaque_zero(), lane = tid & 63, wave = tid >> 6;
   __builtin_assume(tid >= 0 && tid < RC::kThreads);
   const int ln = lane & 31, lh = lane >> 5;
@@ -573,7 +579,7 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   if (n <= 0) return;
   const int L = ctx + n;
   const int R = n * P.G;
-  const int row0 = rg * (32 * NW);
+  const int row0 = rg * (32 * kRowWaves);
   if (row0 >= R) return;
   if (chunk >= nchunks) return;
   const int t_begin = chunk * cb;
@@ -618,7 +624,8 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   }
 
   // ---- this wave's 32 query rows ----
-  const int wrow0 = row0 + 32 * wave;
+  const int slice = SL == 1 ? 0 : wave / kRowWaves;          // which 64 tokens of a staged tile this wave computes
+  const int wrow0 = row0 + 32 * (wave % kRowWaves);
   const bool active = wrow0 < R;                // wave-uniform
   const int row = wrow0 + ln;
   const bool valid = row < R;
@@ -749,7 +756,7 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   f16x8 ph, va[C::kDBlocks];
   float m_safe = 0.f, m_next = -INFINITY, alpha = 1.f, psum = 0.f;
   auto v_frag = [&](int stage, int chunk, int db) {      // chunk = 16-token group 0..3 of the tile
-    const unsigned char* v_rd = smem + stage * RC::kStage + RC::kKBytes + ln * RC::kVStride + 16 * lh;
+    const unsigned char* v_rd = smem + stage * RC::kStage + RC::kKBytes + ln * RC::kVStride + 16 * lh + 2 * RC::kTc * slice;
     return __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(v_rd + 32 * db * RC::kVStride + 32 * chunk));
   };
   // P^T as fp16 (weights lie in [0, 2^8]: 11 significant bits, against 8 of bf16, keep the output's error at the
@@ -770,8 +777,8 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   // First half: S = K Q^T (operand reads from LDS run two steps ahead of the matrix instructions that consume
   // them), mask, row maxima, rescale, the weights of the first 16 tokens.
   auto tile_scores = [&](int stage, int t) __attribute__((always_inline)) {
-    const unsigned char* k_lds = smem + stage * RC::kStage;
-    const int tok0 = t_begin + RC::kT * t;
+    const unsigned char* k_lds = smem + stage * RC::kStage + slice * RC::kTc * RC::kKStride;
+    const int tok0 = t_begin + RC::kT * t + RC::kTc * slice;
     const unsigned char* k_rd = k_lds + ln * RC::kKStride + 16 * lh;
     auto k_frag = [&](int ks, int tb) {
       return as_bf16x8(*reinterpret_cast<const u32x4*>(k_rd + 32 * tb * RC::kKStride + 32 * ks));
@@ -800,7 +807,7 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
 #pragma unroll
     for (int db = 0; db < C::kDBlocks; ++db) va[db] = v_frag(stage, 0, db);
 
-    if (tok0 + RC::kT > ctx) {                   // tile reaches the drafts or the end: apply the mask
+    if (tok0 + RC::kTc > ctx) {                  // tile reaches the drafts or the end: apply the mask
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -875,8 +882,10 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   // clamped to the chunk's last page, their V rows staged as zeros, and they are never computed): with the
   // same number of loads outstanding on every path, the wait before a store covers only the older register
   // set and leaves the newer one in flight.  A branch around an issue would make that wait a full drain.
+  // (a wave of the sliced variant skips a staged tile whose half for it lies past the end)
+  auto mine = [&](int t) { return active && t < ntiles && t_begin + RC::kT * t + RC::kTc * slice < t_end; };
   fetch_pages(0);
-  if constexpr (NW == 8) {
+  if constexpr (NW == 8 && SL == 1) {
     issue_tile(0, krA, vrA);
     issue_tile(1, krB, vrB);
     store_tile(0, 0, krA, vrA);
@@ -884,12 +893,12 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
     __syncthreads();
     for (int t = 0; t < ntiles; t += 2) {
       // LDS stage 0 holds tile t, set B tile t+1, set A tile t+2
-      if (active) { tile_scores(0, t); tile_output(0); }
+      if (mine(t)) { tile_scores(0, t); tile_output(0); }
       store_tile(1, t + 1, krB, vrB);
       issue_tile(t + 3, krB, vrB);
       __syncthreads();
       // LDS stage 1 holds tile t+1, set A tile t+2, set B tile t+3
-      if (active && t + 1 < ntiles) { tile_scores(1, t + 1); tile_output(1); }
+      if (mine(t + 1)) { tile_scores(1, t + 1); tile_output(1); }
       store_tile(0, t + 2, krA, vrA);
       issue_tile(t + 4, krA, vrA);
       __syncthreads();
@@ -902,20 +911,48 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
     issue_tile(1, krA, vrA);
     __syncthreads();
     for (int t = 0; t < ntiles; t += 2) {
-      if (active) { tile_scores(0, t); tile_output(0); }
+      if (mine(t)) { tile_scores(0, t); tile_output(0); }
       store_tile(1, t + 1, krA, vrA);
       issue_tile(t + 2, krA, vrA);
       __syncthreads();
-      if (active && t + 1 < ntiles) { tile_scores(1, t + 1); tile_output(1); }
+      if (mine(t + 1)) { tile_scores(1, t + 1); tile_output(1); }
       store_tile(0, t + 2, krA, vrA);
       issue_tile(t + 3, krA, vrA);
       __syncthreads();
     }
   }
 
+  l_run = half_sum(l_run);
+  if constexpr (SL == 2) {
+    // ---- the wave that took the upper halves of the tiles hands (m, l, O) to the one that took the lower halves
+    // (the tile memory is free: the loop ended with a barrier); accumulator registers go over as they are, one
+    // 256-byte row of LDS per register ----
+    float* xo = reinterpret_cast<float*>(smem) + (wave % kRowWaves) * (C::kDBlocks * 16 + 2) * 64;
+    if (slice == 1 && active) {
+#pragma unroll
+      for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xo[(db * 16 + r) * 64 + lane] = oacc[db][r];
+      xo[(C::kDBlocks * 16) * 64 + lane] = m_run;
+      xo[(C::kDBlocks * 16 + 1) * 64 + lane] = l_run;
+    }
+    __syncthreads();
+    if (slice == 1) return;
+    if (active) {
+      const float m2 = xo[(C::kDBlocks * 16) * 64 + lane], l2 = xo[(C::kDBlocks * 16 + 1) * 64 + lane];
+      const float M = fmaxf(m_run, m2);
+      const float f1 = m_run == -INFINITY ? 0.f : fast_exp2(m_run - M);
+      const float f2 = m2 == -INFINITY ? 0.f : fast_exp2(m2 - M);
+#pragma unroll
+      for (int db = 0; db < C::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] = oacc[db][r] * f1 + xo[(db * 16 + r) * 64 + lane] * f2;
+      l_run = l_run * f1 + l2 * f2;
+      m_run = M;
+    }
+  }
   // ---- write this wave's rows ----
   if (!active) return;
-  l_run = half_sum(l_run);
   if (!valid) return;
   // The weights were truncated to fp16 (round toward zero): every one is low by a factor that is uniform in
   // [0, 2^-11], 2^-12 on average, while the denominator l was summed from the unrounded weights.  The
@@ -960,7 +997,7 @@ __device__ __forceinline__ void rows_item(const AttnParams& P, unsigned char* sm
   }
 }
 
-template <int D, int NW, bool WIDE>
+template <int D, int NW, bool WIDE, int SL>
 __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(AttnParams P) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
@@ -982,8 +1019,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 ? 2 : 1)) void attn_rows_kernel(A
   const int ctx = P.ctx_len[b];
   const int L = ctx + n;
   const int nchunks = max(1, (L + P.chunk_tokens - 1) / P.chunk_tokens);
-  const int cb = (((L + nchunks - 1) / nchunks) + RowsCfg<D, NW>::kT - 1) & ~(RowsCfg<D, NW>::kT - 1);
-  rows_item<D, NW, WIDE>(P, smem, b, static_cast<int>(by), chunk, rg, nchunks, cb, q0, n, ctx);
+  const int cb = (((L + nchunks - 1) / nchunks) + RowsCfg<D, NW, SL>::kT - 1) & ~(RowsCfg<D, NW, SL>::kT - 1);
+  rows_item<D, NW, WIDE, SL>(P, smem, b, static_cast<int>(by), chunk, rg, nchunks, cb, q0, n, ctx);
 }
 
 // Sorted-work-list launch for batches of up to kPlanMaxB requests with ragged lengths.  The grid
@@ -1136,15 +1173,26 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   if (max_rows <= 64 || (max_rows <= 128 && ragged0 && a.B <= kPlanMaxB)) { p.kind = 0; p.rows_per_wg = 128; }
   else if (max_rows <= 128 || a.D != 128) { p.kind = 1; p.rows_per_wg = 128; }
   else { p.kind = 2; p.rows_per_wg = 256; }
+  // Few (request, KV head) pairs with many rows each: 256-row workgroups would have to cut the context to fill
+  // the chip (partial results through memory and a combine kernel).  The sliced variant gives every pair twice
+  // the workgroups instead - 128 rows each, the token halves of every tile split between two waves - when one
+  // such workgroup per compute unit covers the batch.
+  if (p.kind == 2) {
+    const int64_t groups256 = static_cast<int64_t>(a.B) * a.Hkv * ((max_rows + 255) / 256);
+    const int64_t groups128 = static_cast<int64_t>(a.B) * a.Hkv * ((max_rows + 127) / 128);
+    const int n_cu = current_device_cus();
+    if (groups256 * 4 <= 3 * static_cast<int64_t>(n_cu) && groups128 <= n_cu + n_cu / 4) { p.kind = 3; p.rows_per_wg = 128; }
+  }
   const long force_kind = dev_knob("SPECV_ATTN_KIND", -1);            // force a kernel family
   if (force_kind == 1) { p.kind = 1; p.rows_per_wg = 128; }
   if (force_kind == 2 && a.D == 128) { p.kind = 2; p.rows_per_wg = 256; }
   if (force_kind == 0) { p.kind = 0; p.rows_per_wg = 128; }
+  if (force_kind == 3 && a.D == 128 && max_rows > 128) { p.kind = 3; p.rows_per_wg = 128; }
   // more than 64 query nodes per request (two mask words per node): the row-split kernels only
   if (p.wide && p.kind == 0) { p.kind = 1; p.rows_per_wg = 128; }
   p.row_groups = (max_rows + p.rows_per_wg - 1) / p.rows_per_wg;
   const bool token_split = (p.kind == 0);
-  const int gran = token_split ? kTile : 64;              // chunks are whole tiles
+  const int gran = token_split ? kTile : (p.kind == 3 ? 128 : 64);              // chunks are whole tiles
   const int64_t max_tok = static_cast<int64_t>(a.max_pages) * a.page;
   int64_t tok = a.kv_hint > 0 ? a.kv_hint : static_cast<int64_t>(a.B) * max_tok;
   // Chunk length.  Every workgroup pays a fixed prologue/epilogue (and, when a request is split, a
@@ -1164,7 +1212,7 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   chunk = (chunk + gran - 1) / gran * gran;
   if (chunk > max_tok) chunk = (max_tok + gran - 1) / gran * gran;
   // the row-split kernel keeps a chunk's page ids in LDS
-  const int64_t rows_chunk_cap = (p.kind == 2) ? 16384 : 8192;
+  const int64_t rows_chunk_cap = (p.kind >= 2) ? 16384 : 8192;
   if (!token_split && chunk > rows_chunk_cap) chunk = rows_chunk_cap;
   if (chunk < gran) chunk = gran;
   p.chunk_tokens = static_cast<int>(chunk);
@@ -1203,6 +1251,7 @@ const char* attn_plan_name(const AttnPlan& p) {
   if (p.kind == 0) return p.tau > 0 ? "attn_stream_list_kernel (device-built work list sorted by length; token-split body, row-split body from 65 query rows per KV head)"
                                     : "attn_stream_kernel (token-split body, one workgroup per request x KV head x context chunk)";
   if (p.kind == 1) return "attn_rows_kernel<4 waves> (row-split body)";
+  if (p.kind == 3) return "attn_rows_kernel<8 waves, sliced> (row-split body, 128 query rows per workgroup, two waves per 32-row block)";
   return "attn_rows_kernel<8 waves> (row-split body, 256 query rows per workgroup)";
 }
 
@@ -1230,15 +1279,15 @@ static int launch_stream(const AttnParams& P, const AttnPlan& plan, int B, int H
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-template <int D, int NW, bool WIDE>
+template <int D, int NW, bool WIDE, int SL = 1>
 static int launch_rows_as(const AttnParams& P, const AttnPlan& plan, int B, int Hkv, hipStream_t stream) {
-  using RC = RowsCfg<D, NW>;
+  using RC = RowsCfg<D, NW, SL>;
   constexpr size_t kLds = RC::lds_bytes(WIDE);
   static_assert(kLds * (NW == 4 ? 2 : 1) <= 160 * 1024, "row-split kernel: LDS per compute unit");
   static std::atomic<uint64_t> attr_done{0};
-  if (set_lds_once(&attn_rows_kernel<D, NW, WIDE>, kLds, attr_done) != 0) return -6;
+  if (set_lds_once(&attn_rows_kernel<D, NW, WIDE, SL>, kLds, attr_done) != 0) return -6;
   dim3 grid(plan.max_chunks * plan.row_groups, Hkv, B);
-  hipLaunchKernelGGL((attn_rows_kernel<D, NW, WIDE>), grid, dim3(RC::kThreads), kLds, stream, P);
+  hipLaunchKernelGGL((attn_rows_kernel<D, NW, WIDE, SL>), grid, dim3(RC::kThreads), kLds, stream, P);
   return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
@@ -1272,7 +1321,9 @@ int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
   int rc;
   if (plan.kind == 0) rc = a.D == 128 ? launch_stream<128>(P, plan, a.B, a.Hkv, stream) : launch_stream<64>(P, plan, a.B, a.Hkv, stream);
   else if (plan.kind == 1) rc = a.D == 128 ? launch_rows<128, 4>(P, plan, a.B, a.Hkv, stream) : launch_rows<64, 4>(P, plan, a.B, a.Hkv, stream);
-  else rc = launch_rows<128, 8>(P, plan, a.B, a.Hkv, stream);
+  else if (plan.kind == 2) rc = launch_rows<128, 8>(P, plan, a.B, a.Hkv, stream);
+  else rc = plan.wide ? launch_rows_as<128, 8, true, 2>(P, plan, a.B, a.Hkv, stream)
+                      : launch_rows_as<128, 8, false, 2>(P, plan, a.B, a.Hkv, stream);
   if (rc != 0) return rc;
   if (plan.max_chunks > 1) {
     const int max_q = a.max_q > P.n_cap ? P.n_cap : a.max_q;

@@ -156,7 +156,7 @@ struct AttnArgs {
 // The launch plan is a pure function of the descriptor; the workspace-size query and the launch both
 // take the plan object the C-ABI layer computed, so the two can never disagree.
 struct AttnPlan {
-  int kind;           // 0: token-split kernel, 1: row-split, 4 waves, 2: row-split, 8 waves
+  int kind;           // 0: token-split kernel, 1: row-split, 4 waves, 2: row-split, 8 waves, 3: row-split, 8 waves, sliced
   int rows_per_wg;
   int row_groups;
   int chunk_tokens;

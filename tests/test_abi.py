@@ -153,6 +153,7 @@ def test_tuned_accept_and_plan_descriptions_need_no_gpu():
                              max_q_per_req=64, max_pages_per_req=260, total_kv_tokens_hint=16 * 4160)
     text = sv.spec_describe_attn_plan(desc)
     assert "attn_" in text and "chunks" in text
+    assert "sliced" in text and "at most 1 per request" in text   # 128 pairs x 256 rows: two workgroups per pair, no context cut
     text = sv.spec_describe_accept_plan(16, 128256, 1024, 64, True)
     assert "accept_cluster_kernel" in text
     text = sv.spec_describe_accept_plan(16, 128256, 1024, 64, True, target_dtype=sv.SPEC_F32)
