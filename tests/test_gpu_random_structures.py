@@ -52,7 +52,7 @@ def random_structure(rng, B, n_max, ctx_max, linear):
 SHAPES = [(8, 2, 128), (4, 4, 128), (8, 1, 128), (4, 2, 64), (2, 2, 64)]      # (query heads, KV heads, head_dim)
 
 
-@pytest.mark.parametrize("seed", [1, 7, 23])
+@pytest.mark.parametrize("seed", [1, 7, 23, 41, 59])
 def test_random_structures_match_oracle(mods, seed):
     sv, runner = mods
     rng = np.random.default_rng(seed)
