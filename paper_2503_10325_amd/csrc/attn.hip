@@ -165,7 +165,7 @@ __device__ __forceinline__ bool list_uses_rows(const AttnParams& P, int n) {
 // Length of a request in the work list's unit, the 32-token tiles one wave of the token-split body streams.
 // For the row-split body 32 tokens count P.list_rows_units eighths of a unit: batches of equal requests
 // measure 5/8 (a 64-token tile takes 1.25 times a 32-token one), ragged batches of both kinds run best
-// with 3/8 to 4/8; the host passes 4.
+// with 3/8 (seven seeds of the serving mix: 1 to 8 % ahead of 4/8); the host passes 3.
 __device__ __forceinline__ int request_units(const AttnParams& P, int L, int n) {
   const int tiles = (L + kTile - 1) / kTile;
   if (list_uses_rows(P, n)) return (tiles * P.list_rows_units + 7) / 8;
@@ -1225,7 +1225,7 @@ AttnPlan make_attn_plan(const AttnArgs& a) {
   // request says whether they do.
   const bool ragged = a.kv_hint > 0 && a.kv_hint * 100 < static_cast<int64_t>(85) * a.B * max_tok;
   // (the list kernel packs a request's first query row into 16 bits)
-  int tau = (token_split && a.B <= kPlanMaxB && a.total_q < 65536 && ragged) ? 48 : 0;   // with the alternating hand-out below: 44-56 measured best
+  int tau = (token_split && a.B <= kPlanMaxB && a.total_q < 65536 && ragged) ? 44 : 0;   // with the alternating hand-out below: 40-48 measured best
   const long tau_knob = dev_knob("SPECV_ATTN_TAU", -1);   // 0: grid-mapped launch
   if (token_split && a.B <= kPlanMaxB && a.total_q < 65536 && tau_knob >= 0 && tau_knob <= 255) tau = static_cast<int>(tau_knob);
   if (jobs_knob > 0) tau = 0;
@@ -1312,7 +1312,7 @@ int launch_attn(const AttnArgs& a, const AttnPlan& plan, hipStream_t stream) {
   P.chunk_tokens = plan.chunk_tokens; P.max_chunks = plan.max_chunks; P.tau = plan.tau;
   // work list: from 65 query rows per KV head (three 32-row blocks) on, a request runs the row-split body
   P.list_rows_min = plan.tau > 0 ? static_cast<int>(dev_knob("SPECV_ATTN_LIST_ROWS", 65)) : 0;
-  P.list_rows_units = static_cast<int>(dev_knob("SPECV_ATTN_ROWS_UNITS", 4));
+  P.list_rows_units = static_cast<int>(dev_knob("SPECV_ATTN_ROWS_UNITS", 3));
   P.n_cap = plan.wide ? kMaxQWide : kMaxQ;
   P.xcd_swizzle = (plan.kind != 0 && plan.row_groups > 1 &&
                    (static_cast<int64_t>(plan.max_chunks) * plan.row_groups * a.Hkv * a.B) % 8 == 0) ? 1 : 0;
