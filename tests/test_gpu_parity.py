@@ -92,6 +92,26 @@ def test_attention_launch_modes(rt, name, hint):
     assert np.abs(dev.lse.cpu().numpy() - ref_lse).max() < 2e-2
 
 
+def test_attention_256_row_workgroups_with_a_context_cut(rt):
+    """Enough (request, KV head, 256-row group) triples that the plan keeps 256-row workgroups (not the sliced
+    variant) and still cuts the context in two: the partial-result path of the eight-wave row-split kernel and
+    the combine kernel behind it."""
+    from paper_2503_10325_amd import binding as sv
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=13, ctx=("uniform", 300, 700), draft=("tree", (4, 4, 2, 2), 116))
+    a = W.make_attn_inputs(cfg, seed=17)
+    dev = rt.DeviceAttn(a)
+    plan = sv.spec_describe_attn_plan(dev.desc)
+    assert "256 query rows per workgroup" in plan and "at most 2 per request" in plan, plan
+    ref, ref_lse = oracle_attn(a)
+    dev.out.fill_(float("nan"))
+    dev.run()
+    torch.cuda.synchronize()
+    got = dev.out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    assert attn_rel_err(got, ref) <= ATTN_TOL
+    assert np.abs(dev.lse.cpu().numpy() - ref_lse).max() < 2e-2
+
+
 def test_attention_fp32_output_and_determinism(rt):
     cfg = ATTN_CASES["ragged_gqa8"]
     a = W.make_attn_inputs(cfg, seed=5)
