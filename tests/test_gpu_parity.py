@@ -92,12 +92,13 @@ def test_attention_launch_modes(rt, name, hint):
     assert np.abs(dev.lse.cpu().numpy() - ref_lse).max() < 2e-2
 
 
-def test_attention_256_row_workgroups_with_a_context_cut(rt):
+@pytest.mark.parametrize("batch,nodes", [(13, 116), (25, 64)])
+def test_attention_256_row_workgroups_with_a_context_cut(rt, batch, nodes):
     """Enough (request, KV head, 256-row group) triples that the plan keeps 256-row workgroups (not the sliced
     variant) and still cuts the context in two: the partial-result path of the eight-wave row-split kernel and
-    the combine kernel behind it."""
+    the combine kernel behind it, with one and with two ancestor-mask words per node."""
     from paper_2503_10325_amd import binding as sv
-    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=13, ctx=("uniform", 300, 700), draft=("tree", (4, 4, 2, 2), 116))
+    cfg = W.scaled(C["c2_tree_llama3_8b"], batch=batch, ctx=("uniform", 300, 700), draft=("tree", (4, 4, 2, 2), nodes))
     a = W.make_attn_inputs(cfg, seed=17)
     dev = rt.DeviceAttn(a)
     plan = sv.spec_describe_attn_plan(dev.desc)
